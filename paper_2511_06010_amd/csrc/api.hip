@@ -1,0 +1,162 @@
+// C entry points: host-side validation, workspace carving and kernel dispatch.
+#include <cstdlib>
+#include <cstring>
+
+#include "moska_internal.h"
+
+namespace moska {
+
+bool use_mfma_path(const moska_problem_t &p) {
+    static const bool force_generic = [] {
+        const char *e = std::getenv("MOSKA_FORCE_GENERIC");
+        return e && e[0] == '1';
+    }();
+    return !force_generic && p.q_dtype == MOSKA_BF16 && p.D == 128;
+}
+
+int shared_tile_rows(const moska_problem_t &p) {
+    if (!use_mfma_path(p)) return 16;
+    // mean rows per bucket; a tile should hold a typical bucket so its chunk is streamed once
+    const double mean = (double)p.B * p.k * (p.Hq / p.Hkv) / p.C;
+    if (mean <= 12.0) return 16;
+    if (mean <= 24.0) return 32;
+    return 64;
+}
+
+static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+Workspace carve_workspace(const moska_problem_t &p, void *ws) {
+    Workspace w;
+    const size_t items = (size_t)p.B * p.Hkv * p.k, nb = (size_t)p.Hkv * p.C;
+    const size_t tmax = (size_t)max_tiles(p, 16);          // bound valid for every tile size >= 16
+    char *base = (char *)ws;
+    size_t o = 0;
+    w.tile_hdr = (int32_t *)(base + o); o += align_up(4 * sizeof(int32_t));
+    w.tiles = (int32_t *)(base + o);    o += align_up(2 * tmax * sizeof(int32_t));
+    w.rank = (int32_t *)(base + o);     o += align_up(items * sizeof(int32_t));
+    w.off = (int32_t *)(base + o);      o += align_up((nb + 1) * sizeof(int32_t));
+    w.items = (int32_t *)(base + o);    o += align_up(items * sizeof(int32_t));
+    w.bytes = o;
+    return w;
+}
+
+static int check_problem(const moska_problem_t *p) {
+    if (!p) return MOSKA_ERR_INVALID_ARG;
+    if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->D < 1 || p->C < 1 || p->L < 1 || p->k < 1 || p->U_max < 0)
+        return MOSKA_ERR_INVALID_ARG;
+    if (p->Hq % p->Hkv != 0 || p->k > p->C || !(p->scale > 0.f)) return MOSKA_ERR_INVALID_ARG;
+    if (p->D % 16 != 0 || p->D > 256) return MOSKA_ERR_UNSUPPORTED;
+    const bool f32 = p->q_dtype == MOSKA_F32 && p->shared_kv_dtype == MOSKA_F32;
+    const bool b16 = p->q_dtype == MOSKA_BF16 &&
+                     (p->shared_kv_dtype == MOSKA_BF16 || p->shared_kv_dtype == MOSKA_FP8_E4M3);
+    if (!f32 && !b16) return MOSKA_ERR_UNSUPPORTED;
+    if ((int64_t)p->C + p->D > 16384) return MOSKA_ERR_UNSUPPORTED;
+    // index arithmetic inside one head uses int32 item numbers
+    if ((int64_t)p->B * p->Hkv * p->k > (int64_t)1 << 30 || (int64_t)p->B * p->Hq * (p->k + 1) > (int64_t)1 << 30)
+        return MOSKA_ERR_UNSUPPORTED;
+    return MOSKA_OK;
+}
+
+}  // namespace moska
+
+using namespace moska;
+
+extern "C" {
+
+const char *moska_status_string(int status) {
+    switch (status) {
+    case MOSKA_OK: return "ok";
+    case MOSKA_ERR_INVALID_ARG: return "invalid argument";
+    case MOSKA_ERR_UNSUPPORTED: return "unsupported dtype or size";
+    case MOSKA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case MOSKA_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+int moska_workspace_bytes(const moska_problem_t *p, size_t *out) {
+    if (!out) return MOSKA_ERR_INVALID_ARG;
+    if (int rc = check_problem(p)) return rc;
+    *out = carve_workspace(*p, nullptr).bytes;
+    return MOSKA_OK;
+}
+
+int moska_route(const moska_problem_t *p, const void *Q, const void *E, int32_t *ids, float *scores, void *stream) {
+    if (int rc = check_problem(p)) return rc;
+    if (!Q || !E || !ids) return MOSKA_ERR_INVALID_ARG;
+    return launch_route(*p, Q, E, ids, scores, (hipStream_t)stream);
+}
+
+int moska_bucket(const moska_problem_t *p, const int32_t *ids, int32_t *bucket_off, int32_t *bucket_items, void *ws,
+                 size_t ws_bytes, void *stream) {
+    if (int rc = check_problem(p)) return rc;
+    if (!ids || !bucket_off || !bucket_items || !ws) return MOSKA_ERR_INVALID_ARG;
+    const Workspace w = carve_workspace(*p, ws);
+    if (ws_bytes < w.bytes) return MOSKA_ERR_WORKSPACE_TOO_SMALL;
+    return launch_bucket(*p, ids, bucket_off, bucket_items, w.rank, (hipStream_t)stream);
+}
+
+int moska_shared_attn(const moska_problem_t *p, const void *Q, const void *Ks, const void *Vs, const float *scale_k,
+                      const float *scale_v, const int32_t *ids, const int32_t *bucket_off,
+                      const int32_t *bucket_items, float *part_O, float *part_LSE, void *ws, size_t ws_bytes,
+                      void *stream) {
+    if (int rc = check_problem(p)) return rc;
+    if (!Q || !Ks || !Vs || !part_O || !part_LSE || !ws) return MOSKA_ERR_INVALID_ARG;
+    const bool fp8 = p->shared_kv_dtype == MOSKA_FP8_E4M3;
+    if (fp8 && (!scale_k || !scale_v)) return MOSKA_ERR_INVALID_ARG;
+    if (!fp8) scale_k = scale_v = nullptr;
+    if (bucket_off ? !bucket_items : !ids) return MOSKA_ERR_INVALID_ARG;
+    const Workspace w = carve_workspace(*p, ws);
+    if (ws_bytes < w.bytes) return MOSKA_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t s = (hipStream_t)stream;
+    if (!bucket_off) {
+        if (int rc = launch_bucket(*p, ids, w.off, w.items, w.rank, s)) return rc;
+        bucket_off = w.off;
+        bucket_items = w.items;
+    }
+    const int MT = shared_tile_rows(*p);
+    if (int rc = launch_tile_list(*p, bucket_off, MT, w.tile_hdr, w.tiles, s)) return rc;
+    SharedArgs a{Q, Ks, Vs, scale_k, scale_v, bucket_off, bucket_items, w.tile_hdr, w.tiles, part_O, part_LSE};
+    return use_mfma_path(*p) ? launch_shared_mfma(*p, a, MT, s) : launch_shared_generic(*p, a, MT, s);
+}
+
+int moska_unique_attn(const moska_problem_t *p, const void *Q, const void *Ku, const void *Vu,
+                      const int32_t *unique_len, float *part_O, float *part_LSE, void *ws, size_t ws_bytes,
+                      void *stream) {
+    if (int rc = check_problem(p)) return rc;
+    if (!Q || !part_O || !part_LSE) return MOSKA_ERR_INVALID_ARG;
+    if (p->U_max > 0 && (!Ku || !Vu)) return MOSKA_ERR_INVALID_ARG;
+    (void)ws;
+    (void)ws_bytes;
+    UniqueArgs a{Q, Ku, Vu, unique_len, part_O, part_LSE};
+    hipStream_t s = (hipStream_t)stream;
+    return use_mfma_path(*p) ? launch_unique_mfma(*p, a, s) : launch_unique_generic(*p, a, s);
+}
+
+int moska_merge(const moska_problem_t *p, const float *part_O, const float *part_LSE, void *O, float *LSE,
+                void *stream) {
+    if (int rc = check_problem(p)) return rc;
+    if (!part_O || !part_LSE || !O) return MOSKA_ERR_INVALID_ARG;
+    return launch_merge(*p, part_O, part_LSE, O, LSE, (hipStream_t)stream);
+}
+
+int moska_decode_step(const moska_problem_t *p, const void *Q, const void *E, const void *Ks, const void *Vs,
+                      const float *scale_k, const float *scale_v, const void *Ku, const void *Vu,
+                      const int32_t *unique_len, int32_t *ids, int32_t *bucket_off, int32_t *bucket_items,
+                      float *part_O, float *part_LSE, void *O, float *LSE, void *ws, size_t ws_bytes, void *stream) {
+    if (int rc = check_problem(p)) return rc;
+    if (!Q || !E || !Ks || !Vs || !ids || !bucket_off || !bucket_items || !part_O || !part_LSE || !O || !ws)
+        return MOSKA_ERR_INVALID_ARG;
+    if (p->U_max > 0 && (!Ku || !Vu)) return MOSKA_ERR_INVALID_ARG;
+    if (p->shared_kv_dtype == MOSKA_FP8_E4M3 && (!scale_k || !scale_v)) return MOSKA_ERR_INVALID_ARG;
+    if (ws_bytes < carve_workspace(*p, ws).bytes) return MOSKA_ERR_WORKSPACE_TOO_SMALL;
+    if (int rc = moska_route(p, Q, E, ids, nullptr, stream)) return rc;
+    if (int rc = moska_bucket(p, ids, bucket_off, bucket_items, ws, ws_bytes, stream)) return rc;
+    if (int rc = moska_shared_attn(p, Q, Ks, Vs, scale_k, scale_v, ids, bucket_off, bucket_items, part_O, part_LSE, ws,
+                                   ws_bytes, stream))
+        return rc;
+    if (int rc = moska_unique_attn(p, Q, Ku, Vu, unique_len, part_O, part_LSE, ws, ws_bytes, stream)) return rc;
+    return moska_merge(p, part_O, part_LSE, O, LSE, stream);
+}
+
+}  // extern "C"

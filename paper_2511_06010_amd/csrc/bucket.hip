@@ -1,0 +1,160 @@
+// moska_bucket: query aggregation (paper Sec. III-A) as a deterministic counting sort without
+// atomics, and the work-tile list the shared-attention kernels consume.
+//
+// One workgroup per KV head (buckets of different heads never mix, and head h owns exactly
+// B*k items, so its output range starts at h*B*k).  The NW waves of the group take contiguous
+// slices of the head's items in index order.  Inside a wave, lanes that hold the same chunk id
+// find each other with ballots over the id's bits; the lowest such lane bumps the wave's private
+// LDS histogram, and every lane derives its rank inside (wave, chunk).  After a barrier the
+// histograms are prefix-summed over waves and over chunks, giving each item its final position:
+// ascending item index inside every bucket, bit-identical from run to run.
+#include "moska_internal.h"
+
+namespace moska {
+namespace {
+
+// Exclusive scan of v over the block's threads (blockDim.x <= 1024); every thread gets its
+// prefix, *total the grand sum.  tmp: blockDim.x ints of LDS.
+__device__ int block_exclusive_scan(int v, int *tmp, int *total) {
+    const int t = threadIdx.x, n = blockDim.x;
+    tmp[t] = v;
+    __syncthreads();
+    for (int d = 1; d < n; d <<= 1) {
+        const int add = t >= d ? tmp[t - d] : 0;
+        __syncthreads();
+        tmp[t] += add;
+        __syncthreads();
+    }
+    const int incl = tmp[t];
+    *total = tmp[n - 1];
+    __syncthreads();
+    return incl - v;
+}
+
+__global__ __launch_bounds__(1024) void bucket_kernel(const int32_t *__restrict__ ids, int32_t *__restrict__ off,
+                                                       int32_t *__restrict__ items, int32_t *__restrict__ rank,
+                                                       int B, int Hkv, int C, int k, int nbits) {
+    extern __shared__ int lds[];
+    const int NW = blockDim.x / kWave, wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int h = blockIdx.x;
+    const int n = B * k;                          // items of this head
+    int *hist = lds;                              // [NW][C]
+    int *coff = lds + NW * C;                     // [C] exclusive chunk offsets
+    int *tmp = coff + C;                          // [blockDim.x]
+
+    for (int i = threadIdx.x; i < NW * C; i += blockDim.x) hist[i] = 0;
+    __syncthreads();
+
+    const int slice = ((n + NW - 1) / NW + kWave - 1) / kWave * kWave;
+    const int lo = wave * slice, hi = min(n, lo + slice);
+    int *myhist = hist + wave * C;
+    const uint64_t below = (1ull << lane) - 1ull;
+    for (int i0 = lo; i0 < hi; i0 += kWave) {
+        const int i = i0 + lane;
+        const bool valid = i < hi;
+        int c = 0;
+        if (valid) {
+            const int b = i / k, j = i - b * k;
+            c = ids[((int64_t)b * Hkv + h) * k + j];
+        }
+        uint64_t peers = __ballot(valid);
+        for (int bit = 0; bit < nbits; ++bit) {
+            const bool one = (c >> bit) & 1;
+            const uint64_t m = __ballot(one);
+            peers &= one ? m : ~m;
+        }
+        if (valid) {
+            const int r = __popcll(peers & below);
+            const int base = myhist[c];           // same-wave LDS accesses execute in order
+            rank[(int64_t)h * n + i] = base + r;
+            if (r == 0) myhist[c] = base + __popcll(peers);
+        }
+    }
+    __syncthreads();
+
+    // prefix over waves per chunk, chunk totals, then prefix over chunks
+    const int per = (C + blockDim.x - 1) / blockDim.x;
+    const int c0 = threadIdx.x * per, c1 = min(C, c0 + per);
+    int mine = 0;
+    for (int c = c0; c < c1; ++c) {
+        int run = 0;
+        for (int w = 0; w < NW; ++w) {
+            const int t = hist[w * C + c];
+            hist[w * C + c] = run;
+            run += t;
+        }
+        coff[c] = run;
+        mine += run;
+    }
+    int total;
+    int pre = block_exclusive_scan(mine, tmp, &total);
+    for (int c = c0; c < c1; ++c) {
+        const int t = coff[c];
+        coff[c] = pre;
+        off[h * C + c] = h * n + pre;
+        pre += t;
+    }
+    if (threadIdx.x == 0 && h == Hkv - 1) off[Hkv * C] = Hkv * n;
+    __syncthreads();
+
+    for (int i0 = lo; i0 < hi; i0 += kWave) {
+        const int i = i0 + lane;
+        if (i < hi) {
+            const int b = i / k, j = i - b * k;
+            const int c = ids[((int64_t)b * Hkv + h) * k + j];
+            items[(int64_t)h * n + coff[c] + myhist[c] + rank[(int64_t)h * n + i]] = i;
+        }
+    }
+}
+
+// Tiles of up to MT rows per bucket: entry t = (bucket, first row).  hdr[0] = tile count.
+__global__ __launch_bounds__(1024) void tile_list_kernel(const int32_t *__restrict__ off, int NB, int G, int MT,
+                                                          int32_t *__restrict__ hdr, int32_t *__restrict__ tiles) {
+    __shared__ int tmp[1024];
+    const int per = (NB + blockDim.x - 1) / blockDim.x;
+    const int b0 = threadIdx.x * per, b1 = min(NB, b0 + per);
+    int mine = 0;
+    for (int b = b0; b < b1; ++b) mine += ((off[b + 1] - off[b]) * G + MT - 1) / MT;
+    int total;
+    int pre = block_exclusive_scan(mine, tmp, &total);
+    for (int b = b0; b < b1; ++b) {
+        const int rows = (off[b + 1] - off[b]) * G;
+        for (int r = 0; r < rows; r += MT, ++pre) {
+            tiles[2 * pre] = b;
+            tiles[2 * pre + 1] = r;
+        }
+    }
+    if (threadIdx.x == 0) hdr[0] = total;
+}
+
+}  // namespace
+
+int launch_bucket(const moska_problem_t &p, const int32_t *ids, int32_t *off, int32_t *items, int32_t *rank,
+                  hipStream_t s) {
+    // LDS: NW*C (histograms) + C (offsets) + threads (scan) ints; take as many waves as fit in 144 KiB
+    int NW = 16;
+    auto need = [&](int nw) { return ((size_t)nw * p.C + p.C + (size_t)nw * kWave) * sizeof(int); };
+    while (NW > 1 && need(NW) > 144u * 1024u) NW >>= 1;
+    if (need(NW) > 144u * 1024u) return MOSKA_ERR_UNSUPPORTED;
+    const int64_t per_head = (int64_t)p.B * p.k;
+    while (NW > 1 && (int64_t)(NW / 2) * kWave >= per_head) NW >>= 1;   // no point in idle waves
+    int nbits = 0;
+    while ((1 << nbits) < p.C) ++nbits;
+    const size_t lds = need(NW);
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)bucket_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds);
+        if (e != hipSuccess) return MOSKA_ERR_HIP;
+    }
+    hipLaunchKernelGGL(bucket_kernel, dim3(p.Hkv), dim3(NW * kWave), lds, s, ids, off, items, rank, p.B, p.Hkv, p.C,
+                       p.k, nbits);
+    return hip_status(hipGetLastError());
+}
+
+int launch_tile_list(const moska_problem_t &p, const int32_t *off, int MT, int32_t *hdr, int32_t *tiles,
+                     hipStream_t s) {
+    hipLaunchKernelGGL(tile_list_kernel, dim3(1), dim3(1024), 0, s, off, p.Hkv * p.C, p.Hq / p.Hkv, MT, hdr, tiles);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace moska

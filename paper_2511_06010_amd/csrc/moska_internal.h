@@ -1,0 +1,90 @@
+// Internal declarations shared by the library's translation units (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moska.h"
+
+namespace moska {
+
+constexpr int kWave = 64;
+
+// Rows per work tile of the shared-attention kernels (a tile = up to MT query rows of one
+// bucket streamed against that bucket's chunk).
+int shared_tile_rows(const moska_problem_t &p);
+bool use_mfma_path(const moska_problem_t &p);
+
+// Upper bound on the number of tiles for this problem at MT rows per tile.
+inline int64_t max_tiles(const moska_problem_t &p, int MT) {
+    const int64_t items = (int64_t)p.B * p.Hkv * p.k;
+    const int64_t nb = (int64_t)p.Hkv * p.C;
+    const int64_t G = p.Hq / p.Hkv;
+    return (items < nb ? items : nb) + (items * G) / MT;
+}
+
+// Workspace layout (int32 units unless noted), one region per user:
+//   [tile header 4][tile list 2*Tmax][bucket rank scratch n_items][internal bucket_off NB+1]
+//   [internal bucket_items n_items]
+struct Workspace {
+    int32_t *tile_hdr;      // [0] = number of tiles
+    int32_t *tiles;         // (bucket, first row) pairs
+    int32_t *rank;          // moska_bucket scratch
+    int32_t *off;           // bucket_off when the caller passes none
+    int32_t *items;
+    size_t bytes;
+};
+Workspace carve_workspace(const moska_problem_t &p, void *ws);
+
+int launch_route(const moska_problem_t &p, const void *Q, const void *E, int32_t *ids, float *scores,
+                 hipStream_t s);
+int launch_bucket(const moska_problem_t &p, const int32_t *ids, int32_t *off, int32_t *items,
+                  int32_t *rank_scratch, hipStream_t s);
+int launch_tile_list(const moska_problem_t &p, const int32_t *off, int MT, int32_t *hdr, int32_t *tiles,
+                     hipStream_t s);
+
+struct SharedArgs {
+    const void *Q, *Ks, *Vs;
+    const float *scale_k, *scale_v;
+    const int32_t *off, *items, *tile_hdr, *tiles;
+    float *part_O, *part_LSE;
+};
+struct UniqueArgs {
+    const void *Q, *Ku, *Vu;
+    const int32_t *unique_len;
+    float *part_O, *part_LSE;
+};
+int launch_shared_generic(const moska_problem_t &p, const SharedArgs &a, int MT, hipStream_t s);
+int launch_unique_generic(const moska_problem_t &p, const UniqueArgs &a, hipStream_t s);
+int launch_shared_mfma(const moska_problem_t &p, const SharedArgs &a, int MT, hipStream_t s);
+int launch_unique_mfma(const moska_problem_t &p, const UniqueArgs &a, hipStream_t s);
+int launch_merge(const moska_problem_t &p, const float *part_O, const float *part_LSE, void *O, float *LSE,
+                 hipStream_t s);
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? MOSKA_OK : MOSKA_ERR_HIP; }
+
+// ---- storage dtype helpers (device) ----------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// round-to-nearest-even f32 -> bf16 bits (inputs here are finite)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// OCP e4m3fn byte -> f32, exact
+__device__ __forceinline__ float fp8_e4m3fn_to_f32(uint32_t b) {
+    const uint32_t s = (b & 0x80u) << 24, e = (b >> 3) & 15u, m = b & 7u;
+    if (e == 0) return __uint_as_float(s | __float_as_uint((float)m * 0.001953125f));
+    return __uint_as_float(s | ((e + 120u) << 23) | (m << 20));   // 0x7F decodes as 480, not NaN: unsupported input
+}
+
+template <int DT>
+__device__ __forceinline__ float load_f32(const void *p, int64_t i) {
+    if constexpr (DT == MOSKA_F32) return ((const float *)p)[i];
+    else if constexpr (DT == MOSKA_BF16) return bf16_bits_to_f32(((const uint16_t *)p)[i]);
+    else return fp8_e4m3fn_to_f32(((const uint8_t *)p)[i]);
+}
+
+}  // namespace moska

@@ -1,0 +1,207 @@
+"""GPU-vs-oracle parity through the C interface (needs an MI355X; run with -m gpu)."""
+import math
+
+import pytest
+import torch
+
+import oracle
+import paper_2511_06010_amd as moska
+from moska_inputs import Problem, config, generate
+from parity import (assert_lse_close, assert_vectors_close, check_against_oracle, check_route, gpu_pipeline,
+                    sub_inputs, tol_key)
+
+pytestmark = pytest.mark.gpu
+
+
+def P(**kw):
+    base = dict(B=8, Hq=8, Hkv=2, D=128, C=8, L=256, k=2, U=128, q_dtype="bf16", kv_dtype="bf16")
+    base.update(kw)
+    return Problem(**base)
+
+
+SMALL = {
+    # the fp32 configuration (vector-ALU path), and variants of it
+    "cfg0": config(0),
+    "f32-ragged-odd": P(q_dtype="f32", kv_dtype="f32", B=7, Hq=6, Hkv=3, D=64, C=5, L=100, k=2, U=77),
+    "f32-d128-k1": P(q_dtype="f32", kv_dtype="f32", B=5, Hq=4, Hkv=4, D=128, C=3, L=65, k=1, U=9),
+    "f32-k-eq-C": P(q_dtype="f32", kv_dtype="f32", B=6, Hq=4, Hkv=2, D=32, C=4, L=130, k=4, U=64),
+    # bf16 on the MFMA path: several tiles, ragged tails, row counts off the tile size
+    "bf16-base": P(),
+    "bf16-ragged": P(B=37, Hq=16, Hkv=4, C=12, L=200, k=3, U=150),
+    "bf16-long-chunk": P(B=9, Hq=8, Hkv=2, C=3, L=1100, k=2, U=1000),
+    "bf16-hot-bucket": P(B=96, Hq=8, Hkv=2, C=2, L=160, k=1, U=40),      # ~190 rows per bucket
+    "bf16-g1": P(B=20, Hq=4, Hkv=4, C=6, L=96, k=2, U=33),
+    "bf16-g8": P(B=11, Hq=16, Hkv=2, C=6, L=96, k=3, U=70),
+    "bf16-g16-k-eq-C": P(B=3, Hq=16, Hkv=1, C=4, L=64, k=4, U=31),
+    "bf16-u0": P(B=6, U=0),
+    "bf16-tiny-L": P(B=6, L=5, U=3),
+    "bf16-scale": P(B=10, scale=0.37),
+    # bf16 with a head size the MFMA kernels do not cover (vector-ALU path)
+    "bf16-d64": P(D=64, B=10, L=150, U=90),
+    # fp8 shared store
+    "fp8-base": P(kv_dtype="fp8", B=24, Hq=16, Hkv=2, C=6, L=300, k=2, U=100),
+    "fp8-hot": P(kv_dtype="fp8", B=80, Hq=16, Hkv=2, C=2, L=128, k=1, U=16),
+    "fp8-d64": P(kv_dtype="fp8", D=64, B=9, L=70, U=20),
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_small_problem_matches_oracle(name):
+    p = SMALL[name]
+    ragged = "ragged" if ("ragged" in name or "odd" in name) else "full"
+    print(f"case {name}: {p}", flush=True)
+    check_against_oracle(generate(p, seed=101, unique_len=ragged), name)
+
+
+def test_zipf_popularity_and_empty_buckets():
+    # strongly skewed targets: one very hot bucket, many buckets that receive nothing
+    p = P(B=64, Hq=8, Hkv=2, C=40, L=96, k=2, U=50, popularity="zipf", zipf_s=2.0)
+    inp = generate(p, seed=5)
+    buf, st = check_against_oracle(inp, "zipf")
+    sizes = (st.bucket_off[1:] - st.bucket_off[:-1])
+    assert (sizes == 0).any() and sizes.max() >= 12
+
+
+def test_batching_invariance():
+    # Sec. III-A: batching the queries of a bucket into one matrix must not change any row --
+    # a request processed alone gives the same partial as in the batch (up to fp32 rounding order)
+    p = P(B=32, C=2, k=1, L=192, U=16)
+    inp = generate(p, seed=7).to("cuda")
+    full = gpu_pipeline(inp)
+    for b in (0, 5, 31):
+        one = generate(p.with_(B=1), seed=7).to("cuda")
+        one.Q, one.Ku, one.Vu = inp.Q[b:b + 1].contiguous(), inp.Ku[b:b + 1].contiguous(), inp.Vu[b:b + 1].contiguous()
+        one.E, one.Ks, one.Vs, one.unique_len = inp.E, inp.Ks, inp.Vs, inp.unique_len[b:b + 1].contiguous()
+        solo = gpu_pipeline(one)
+        assert torch.equal(solo.ids[0], full.ids[b])
+        torch.testing.assert_close(solo.part_O[0], full.part_O[b], rtol=0, atol=2e-6)
+        torch.testing.assert_close(solo.part_LSE[0], full.part_LSE[b], rtol=0, atol=2e-6)
+
+
+def test_run_twice_is_bit_identical():
+    p = P(B=40, Hq=16, Hkv=4, C=10, L=300, k=3, U=200)
+    inp = generate(p, seed=9, unique_len="ragged").to("cuda")
+    a, b = gpu_pipeline(inp), gpu_pipeline(inp)
+    for name in ("ids", "bucket_off", "bucket_items", "part_O", "part_LSE", "O", "LSE"):
+        x, y = getattr(a, name), getattr(b, name)
+        assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), name
+
+
+def test_route_ties_and_zero_query():
+    p = P(B=6, C=9, k=4)
+    inp = generate(p, seed=11)
+    inp.E[:, 7] = inp.E[:, 2]                       # exact ties: lower chunk id first
+    inp.E[:, 8] = inp.E[:, 2]
+    inp.Q[0] = 0                                    # all scores equal: ids 0..k-1
+    o_ids, _, o_all = oracle.route(p, inp.Q, inp.E, want_all_scores=True)
+    d = inp.to("cuda")
+    ids = torch.empty_like(o_ids, device="cuda")
+    moska.route(p, d.Q, d.E, ids)
+    torch.cuda.synchronize()
+    assert torch.equal(ids.cpu(), o_ids)
+    assert ids[0].cpu().tolist() == [[0, 1, 2, 3]] * p.Hkv
+
+
+def test_bucket_handles_many_items_per_wave_slice():
+    p = P(B=700, Hq=4, Hkv=2, C=37, k=5, L=16, U=0, D=64)
+    g = torch.Generator().manual_seed(3)
+    ids = torch.stack([torch.stack([torch.randperm(p.C, generator=g)[:p.k] for _ in range(p.Hkv)])
+                       for _ in range(p.B)]).to(torch.int32)
+    off, items = oracle.bucket(p, ids)
+    buf = moska.Buffers(p)
+    moska.bucket(p, ids.cuda(), buf.bucket_off, buf.bucket_items, buf.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(buf.bucket_off.cpu(), off) and torch.equal(buf.bucket_items.cpu(), items)
+
+
+def test_merge_empty_slots():
+    p = P(B=3, Hq=4, Hkv=2, k=2, D=64)
+    pO = torch.randn(p.B, p.Hq, 3, p.D)
+    pL = torch.randn(p.B, p.Hq, 3)
+    pL[0, :, 1] = -math.inf                          # one empty slot
+    pL[1] = -math.inf                                # a row with nothing at all
+    pO[1] = float("nan")                             # empty slots' O must never be read
+    want_O, want_L = oracle.merge(pO[[0, 2]], pL[[0, 2]])
+    O = torch.empty(p.B, p.Hq, p.D, dtype=torch.bfloat16, device="cuda")
+    LSE = torch.empty(p.B, p.Hq, device="cuda")
+    moska.merge(p, pO.cuda(), pL.cuda(), O, LSE)
+    torch.cuda.synchronize()
+    assert (O[1] == 0).all() and torch.isinf(LSE[1]).all()
+    torch.testing.assert_close(O[[0, 2]].cpu().double(), want_O, rtol=0, atol=2e-2)
+    torch.testing.assert_close(LSE[[0, 2]].cpu().double(), want_L, rtol=0, atol=1e-5)
+
+
+def test_invalid_arguments_are_rejected_before_launch():
+    p = P()
+    buf = moska.Buffers(p)
+    inp = generate(p, seed=1).to("cuda")
+    with pytest.raises(moska.MoskaError, match="invalid"):
+        moska.route(p.with_(k=9), inp.Q, inp.E, torch.empty(p.B, p.Hkv, 9, dtype=torch.int32, device="cuda"))
+    with pytest.raises(moska.MoskaError, match="unsupported"):
+        moska.workspace_bytes(p.with_(D=72))
+    with pytest.raises(moska.MoskaError, match="workspace"):
+        moska.bucket(p, buf.ids, buf.bucket_off, buf.bucket_items, buf.ws[:16])
+    with pytest.raises(moska.MoskaError, match="invalid"):       # fp8 store without scales
+        q = p.with_(kv_dtype="fp8")
+        k8 = torch.zeros(p.C, p.Hkv, p.L, p.D, dtype=torch.uint8, device="cuda").view(torch.float8_e4m3fn)
+        moska.shared_attn(q, inp.Q, k8, k8, None, None, buf.ids, buf.bucket_off, buf.bucket_items, buf.part_O,
+                          buf.part_LSE, buf.ws)
+    torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------- full benchmark sizes
+
+def _full_size_check(cfg_idx: int, n_pairs: int):
+    """Routing and bucketing verified for every item; attention on sampled (request, KV head)
+    pairs (all G heads, all k+1 partials, merged output) that the oracle computes one by one."""
+    p = config(cfg_idx)
+    print(f"full-size config {cfg_idx}: {p}", flush=True)
+    inp = generate(p, seed=20251106 + cfg_idx, device="cuda")
+    o_ids, _, o_all = oracle.route(p, inp.Q.cpu(), inp.E.cpu(), want_all_scores=True)
+    buf = gpu_pipeline(inp)
+    excused = check_route(p, buf.routed_ids, o_ids, o_all)
+    print(f"  route ok ({excused} tie-excused pairs)", flush=True)
+    if excused:
+        buf = gpu_pipeline(inp, ids_override=o_ids.cuda())
+    off, items = oracle.bucket(p, o_ids)
+    assert torch.equal(buf.bucket_off.cpu(), off) and torch.equal(buf.bucket_items.cpu(), items)
+    sizes = (off[1:] - off[:-1]).reshape(p.Hkv, p.C)
+    # sample: the hottest and the coldest non-empty bucket, plus seeded random pairs
+    g = torch.Generator().manual_seed(cfg_idx)
+    pairs = set()
+    flat = sizes.flatten()
+    for bk in (int(flat.argmax()), int(torch.where(flat > 0, flat, flat.max() + 1).argmin())):
+        h, c = divmod(bk, p.C)
+        item = int(items[off[bk]])
+        pairs.add((item // p.k, h))
+        item = int(items[off[bk + 1] - 1])
+        pairs.add((item // p.k, h))
+    while len(pairs) < n_pairs:
+        pairs.add((int(torch.randint(0, p.B, (1,), generator=g)), int(torch.randint(0, p.Hkv, (1,), generator=g))))
+    key = tol_key(p)
+    G = p.G
+    for b, h in sorted(pairs):
+        sub, sub_ids = sub_inputs(inp, o_ids, b, h)
+        st = oracle.decode_step(sub, ids=sub_ids)
+        rows = slice(h * G, (h + 1) * G)
+        assert_vectors_close(buf.part_O[b, rows], st.part_O[0], key, f"cfg{cfg_idx} part_O ({b},{h})")
+        assert_lse_close(buf.part_LSE[b, rows], st.part_LSE[0], key, f"cfg{cfg_idx} part_LSE ({b},{h})")
+        assert_vectors_close(buf.O[b, rows], st.O_direct[0], key, f"cfg{cfg_idx} O ({b},{h})")
+        assert_lse_close(buf.LSE[b, rows], st.LSE_direct[0], key, f"cfg{cfg_idx} LSE ({b},{h})")
+    # properties that hold at any size: every slot written, outputs finite, LSE of the merge
+    # above every partial LSE
+    assert torch.isfinite(buf.part_O).all() and torch.isfinite(buf.part_LSE).all()
+    assert (buf.LSE[..., None] >= buf.part_LSE - 1e-3).all()
+    print(f"  attention ok on {len(pairs)} sampled (request, head) pairs", flush=True)
+    del inp, buf
+    torch.cuda.empty_cache()
+
+
+def test_config1_full():
+    inp = generate(config(1), seed=20251107, device="cuda")
+    check_against_oracle(inp.to("cpu"), "cfg1")
+
+
+@pytest.mark.parametrize("cfg_idx,n_pairs", [(2, 12), (3, 10), (4, 10)])
+def test_full_size_sampled(cfg_idx, n_pairs):
+    _full_size_check(cfg_idx, n_pairs)
