@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoSKA decode-attention hot path on one MI355X.
+
+A step is one pass of the whole path (route -> bucket -> shared attention -> unique attention ->
+merge) over one batch of synthetic requests, inputs resident in HBM.  Default workload: the
+configuration the headline metric is quoted on (batch 256, 1M shared tokens, bf16).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config i] [--no-cpu-baseline]
+
+Prints one JSON line: decode queries/s (value), shared-attention TFLOP/s, per-call times with
+their roofline fractions, the roofline object of the slowest call and the CPU oracle's rate on a
+bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def algorithmic_work(p, bucket_off):
+    """Bytes each call must move and flops it must do, from the problem and the actual bucket
+    occupancy (a bucket's K and V are counted once, however many rows it has)."""
+    esz_q = 4 if p.q_dtype == "f32" else 2
+    esz_kv = {"f32": 4, "bf16": 2, "fp8": 1}[p.kv_dtype]
+    sizes = (bucket_off[1:] - bucket_off[:-1])
+    nonempty = int((sizes > 0).sum())
+    rows_q = p.B * p.Hq
+    shared_rows = rows_q * p.k
+    w = {}
+    w["route"] = dict(bytes=p.B * p.Hq * p.D * esz_q + p.Hkv * p.C * p.D * esz_q + p.B * p.Hkv * p.k * 4,
+                      flops=2.0 * p.B * p.Hkv * p.C * p.D)
+    w["bucket"] = dict(bytes=p.B * p.Hkv * p.k * 4 * 4 + (p.Hkv * p.C + 1) * 4, flops=0.0)
+    w["shared_attn"] = dict(bytes=nonempty * 2 * p.L * p.D * esz_kv + shared_rows * p.D * esz_q
+                            + shared_rows * (p.D + 1) * 4,
+                            flops=4.0 * p.D * shared_rows * p.L)
+    w["unique_attn"] = dict(bytes=2 * p.B * p.Hkv * p.U * p.D * esz_q + rows_q * p.D * esz_q + rows_q * (p.D + 1) * 4,
+                            flops=4.0 * p.D * rows_q * p.U)
+    w["merge"] = dict(bytes=rows_q * ((p.k + 1) * (p.D + 1) * 4 + p.D * esz_q + 4), flops=0.0)
+    return w
+
+
+def read_traffic(name):
+    """HBM traffic per launch measured offline with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE),
+    kept as `kernel workload bytes` lines in profiles/hbm_traffic.txt; None if not recorded."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split("#")[0].split()
+        if len(f) == 3 and (f[0], f[1]) == name:
+            return float(f[2])
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="workload index (2 = the headline configuration)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=0, help="requests in the oracle's sample (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding or collectives are part of it); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2511_06010_amd as moska
+    from moska_inputs import config, generate
+
+    moska.load_library()                       # fails loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    p = config(args.config)
+    inp = generate(p, seed=20251106 + args.config, device="cuda")
+    buf = moska.Buffers(p)
+    torch.cuda.synchronize()
+
+    calls = ["route", "bucket", "shared_attn", "unique_attn", "merge"]
+
+    def step(events=None):
+        rec = (lambda i: events[i].record()) if events is not None else (lambda i: None)
+        rec(0)
+        moska.route(p, inp.Q, inp.E, buf.ids, None)
+        rec(1)
+        moska.bucket(p, buf.ids, buf.bucket_off, buf.bucket_items, buf.ws)
+        rec(2)
+        moska.shared_attn(p, inp.Q, inp.Ks, inp.Vs, inp.scale_k, inp.scale_v, buf.ids, buf.bucket_off,
+                          buf.bucket_items, buf.part_O, buf.part_LSE, buf.ws)
+        rec(3)
+        moska.unique_attn(p, inp.Q, inp.Ku, inp.Vu, inp.unique_len, buf.part_O, buf.part_LSE, buf.ws)
+        rec(4)
+        moska.merge(p, buf.part_O, buf.part_LSE, buf.O, buf.LSE)
+        rec(5)
+
+    for _ in range(args.warmup):
+        step()
+    # events live on torch's current stream, the stream every call is enqueued on
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    per_call_ms = {c: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, c in enumerate(calls)}
+
+    work = algorithmic_work(p, buf.bucket_off.cpu())
+    kernels = {}
+    for c in calls:
+        ms = per_call_ms[c]
+        gbs = work[c]["bytes"] / (ms * 1e-3) / 1e9
+        tfl = work[c]["flops"] / (ms * 1e-3) / 1e12
+        kernels[c] = {"ms": round(ms, 5), "GB/s": round(gbs, 1), "TFLOP/s": round(tfl, 2),
+                      "hbm_frac": round(gbs / HBM_PEAK_GBS, 4), "mfma_frac": round(tfl / MFMA_BF16_PEAK_TFLOPS, 4)}
+    dom = max(("shared_attn", "unique_attn"), key=lambda c: per_call_ms[c])
+    # both attention calls are bound by the bytes the method itself must stream at this workload
+    # (arithmetic intensity ~ rows per bucket flop/B, far left of the 315 flop/B ridge)
+    ach = work[dom]["bytes"] / (per_call_ms[dom] * 1e-3) / 1e9
+    roofline = {"kernel": "moska_" + dom, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                "traffic": read_traffic(("moska_" + dom, p.name))}
+
+    out = {
+        "metric": "shared-attn TFLOP/s + decode queries/s, B=256, 1M shared tokens, 1 GPU",
+        "value": round(p.B / (ms_per_step * 1e-3), 1), "unit": "queries/s",
+        "shared_attn_tflops": kernels["shared_attn"]["TFLOP/s"],
+        "unique_attn_gbs": kernels["unique_attn"]["GB/s"],
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if p.q_dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": p.name, "B": p.B, "Hq": p.Hq, "Hkv": p.Hkv, "D": p.D, "C": p.C, "L": p.L,
+                   "k": p.k, "U": p.U, "shared_kv_dtype": p.kv_dtype, "popularity": p.popularity,
+                   "layers": 1},
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        from moska_inputs import Inputs
+        # bounded sample: the first nb requests (all heads) against the full shared store
+        rows_per_s_guess = 25.0 * oracle.threads()                 # ~40 ms per row per core at this size
+        nb = args.cpu_sample or max(1, min(p.B, int(15.0 * rows_per_s_guess * (36864.0 / (p.k * p.L + p.U)) / p.Hq)))
+        sp = p.with_(B=nb)
+        cpu = lambda t: None if t is None else t.cpu()
+        sub = Inputs(sp, inp.Q[:nb].cpu(), inp.E.cpu(), inp.Ks.cpu(), inp.Vs.cpu(), cpu(inp.scale_k), cpu(inp.scale_v),
+                     inp.Ku[:nb].cpu(), inp.Vu[:nb].cpu(), inp.unique_len[:nb].cpu(), inp.cstar[:nb].cpu())
+        c0 = time.perf_counter()
+        ids, _ = oracle.route(sp, sub.Q, sub.E)
+        oracle.bucket(sp, ids)
+        pO, pL = oracle.partials(sub, ids)
+        O, _ = oracle.merge(pO, pL)
+        c1 = time.perf_counter()
+        err = float((buf.O[:nb].double().cpu() - O).abs().max())
+        out["cpu_baseline"] = {"value": round(nb / (c1 - c0), 3), "unit": "queries/s", "cores": oracle.threads(),
+                               "kind": "oracle", "seconds": round(c1 - c0, 2),
+                               "sample": f"first {nb} of {p.B} requests, all {p.Hq} heads, full shared store; "
+                                         f"max |GPU-oracle| on the sample {err:.2e}"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
