@@ -16,6 +16,10 @@ bool use_mfma_path(const moska_problem_t &p) {
 
 int shared_tile_rows(const moska_problem_t &p) {
     if (!use_mfma_path(p)) return 16;
+    if (const char *e = std::getenv("MOSKA_SHARED_MT")) {   // tuning override: 16, 32 or 64
+        const int mt = std::atoi(e);
+        if (mt == 16 || mt == 32 || mt == 64) return mt;
+    }
     // mean rows per bucket; a tile should hold a typical bucket so its chunk is streamed once
     const double mean = (double)p.B * p.k * (p.Hq / p.Hkv) / p.C;
     if (mean <= 12.0) return 16;
@@ -51,6 +55,9 @@ static int check_problem(const moska_problem_t *p) {
                      (p->shared_kv_dtype == MOSKA_BF16 || p->shared_kv_dtype == MOSKA_FP8_E4M3);
     if (!f32 && !b16) return MOSKA_ERR_UNSUPPORTED;
     if ((int64_t)p->C + p->D > 16384) return MOSKA_ERR_UNSUPPORTED;
+    // byte offsets inside one chunk / one request's unique store are 32-bit in the kernels
+    if ((int64_t)p->L * p->D * 4 >= (int64_t)1 << 32 || (int64_t)p->U_max * p->D * 4 >= (int64_t)1 << 32)
+        return MOSKA_ERR_UNSUPPORTED;
     // index arithmetic inside one head uses int32 item numbers
     if ((int64_t)p->B * p->Hkv * p->k > (int64_t)1 << 30 || (int64_t)p->B * p->Hq * (p->k + 1) > (int64_t)1 << 30)
         return MOSKA_ERR_UNSUPPORTED;

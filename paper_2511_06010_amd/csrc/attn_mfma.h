@@ -1,0 +1,435 @@
+// Device code of the MFMA streaming attention (Shared KV Attention and Unique KV Attention,
+// paper Sec. III-A) for bf16 queries, head size 128 and a bf16 or fp8-e4m3 key/value store.
+//
+// Both are the same streaming problem: up to 16*NR query rows that attend to ONE key set -- the
+// gathered rows of a (chunk, KV head) bucket, or the G heads of one request -- while K and V of
+// that set are read from HBM exactly once.  A workgroup's NW wavefronts split the keys (32-key
+// tiles, interleaved), each keeps all rows' queries and output accumulators in registers, and the
+// waves' partial (max, sum, O) are combined through LDS at the end.  Nothing is staged in LDS on
+// the way in: the global-memory access patterns are chosen so that what a lane loads IS its MFMA
+// operand.
+//
+// v_mfma_f32_16x16x32_bf16 computes C[16x16] += A[16x32] * B[32x16]; lane (q = lane/16,
+// x = lane%16) holds A[x][8q..8q+7], B[8q..8q+7][x] and C[4q..4q+3][x].
+//
+//   S^T = K Q^T      A = 16 keys x 32 dims: lane (q,x) loads 16 B of key row x   (contiguous dims)
+//                    B = Q^T, resident in registers for the whole kernel
+//                    C: lane (q,x) gets keys 4q..4q+3 of row x  -> a softmax row lives in the
+//                       four lanes x, x+16, x+32, x+48: two cross-lane steps per statistic
+//   O^T = V^T P^T    B = P^T: a lane's 8 probabilities (keys 4q..4q+3 of both 16-key blocks of a
+//                       32-key tile) are used as they are -- the contraction order of the keys
+//                       is free as long as V uses the same one
+//                    A = V^T: lane (q,x) loads dims 8x..8x+7 of exactly those 8 keys (each load
+//                       instruction covers four whole 256-byte rows) and transposes the 8x8
+//                       block in registers with byte permutes; MFMA number e (0..7) then takes
+//                       dim 8x+e, so a lane accumulates O[row x][32q .. 32q+31]
+#pragma once
+
+#include "moska_internal.h"
+
+namespace moska {
+namespace mfma {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int HD = 128;                       // head size served here
+constexpr int OSTRIDE = HD + 4;               // LDS row: 128 outputs, max, sum, pad
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr uint32_t kSelLo = 0x05040100u;      // v_perm: (lo16 of b) | (lo16 of a) << 16
+constexpr uint32_t kSelHi = 0x07060302u;      // v_perm: (hi16 of b) | (hi16 of a) << 16
+
+__device__ __forceinline__ f32x4 mfma16(const uint32_t (&a)[4], const uint32_t (&b)[4], f32x4 c) {
+    const u32x4 av = {a[0], a[1], a[2], a[3]}, bv = {b[0], b[1], b[2], b[3]};
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, bv), c,
+                                                   0, 0, 0);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // round to nearest even
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+template <int KVD> constexpr int row_bytes() { return KVD == MOSKA_BF16 ? 2 * HD : HD; }
+
+// the first head dim of the 8 that lane group q contributes to MFMA step kb of S^T = K Q^T
+template <int KVD>
+__device__ __forceinline__ int qk_dim0(int kb, int q) {
+    if constexpr (KVD == MOSKA_BF16) return 32 * kb + 8 * q;         // 16-byte loads of bf16 keys
+    else return 64 * (kb >> 1) + 16 * q + 8 * (kb & 1);              // 16-byte loads of fp8 keys
+}
+
+template <int KVD> struct TileK;
+template <> struct TileK<MOSKA_BF16> { uint4 k[2][4]; };       // [16-key block][kb]
+template <> struct TileK<MOSKA_FP8_E4M3> { uint4 k[2][2]; };   // [16-key block][64-dim half]
+template <int KVD> struct TileV;
+template <> struct TileV<MOSKA_BF16> { uint4 v[8]; };          // [key slot]: dims 8x..8x+7
+template <> struct TileV<MOSKA_FP8_E4M3> { uint2 v[8]; };
+
+// row (inside a 32-key tile) of key slot s (0..7) for lane group q
+__device__ __forceinline__ constexpr int slot_row(int s) { return s < 4 ? s : 12 + s; }   // + 4q
+
+// K and V of a key set are read through raw buffer resources that span exactly the set's
+// nkeys rows: the hardware range check returns zeros for rows past the end, so ragged tails need
+// no clamping (their scores are masked in the softmax).  A load's address is
+// voffset (tile start + the lane's fixed offset) + a compile-time constant.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t key_set_rsrc(const char *base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)bytes, 0x00020000);
+}
+
+// A lane's byte offsets inside a tile; tile t of a key set starts at byte 32*t*ROWB.
+template <int KVD> struct LaneOff {
+    uint32_t k, v;
+    __device__ __forceinline__ LaneOff(int q, int x)
+        : k((uint32_t)(x * row_bytes<KVD>() + 16 * q)),
+          v((uint32_t)(4 * q * row_bytes<KVD>() + (KVD == MOSKA_BF16 ? 16 : 8) * x)) {}
+};
+
+__device__ __forceinline__ uint4 as_uint4(u32x4 v) { return uint4{v[0], v[1], v[2], v[3]}; }
+
+template <int KVD>
+__device__ __forceinline__ void load_k(TileK<KVD> &t, __amdgpu_buffer_rsrc_t rk, const LaneOff<KVD> &lo, int tile) {
+    constexpr int ROWB = row_bytes<KVD>();
+    constexpr int NLD = KVD == MOSKA_BF16 ? 4 : 2;
+    const uint32_t off = (uint32_t)tile * (32u * ROWB) + lo.k;
+#pragma unroll
+    for (int kblk = 0; kblk < 2; ++kblk)
+#pragma unroll
+        for (int i = 0; i < NLD; ++i)
+            t.k[kblk][i] = as_uint4(__builtin_amdgcn_raw_buffer_load_b128(rk, off + kblk * 16 * ROWB + 64 * i, 0, 0));
+}
+
+template <int KVD>
+__device__ __forceinline__ void load_v(TileV<KVD> &t, __amdgpu_buffer_rsrc_t rv, const LaneOff<KVD> &lo, int tile) {
+    constexpr int ROWB = row_bytes<KVD>();
+    const uint32_t off = (uint32_t)tile * (32u * ROWB) + lo.v;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        if constexpr (KVD == MOSKA_BF16) {
+            t.v[s] = as_uint4(__builtin_amdgcn_raw_buffer_load_b128(rv, off + slot_row(s) * ROWB, 0, 0));
+        } else {
+            const auto w = __builtin_amdgcn_raw_buffer_load_b64(rv, off + slot_row(s) * ROWB, 0, 0);
+            t.v[s] = uint2{w[0], w[1]};
+        }
+    }
+}
+
+template <int NR> struct WaveState {
+    f32x4 o[NR][8];     // [row block][e]: O[row 16rb+x][32q + 8r + e] in component r
+    float m[NR], l[NR]; // running max (log2 domain) and this lane's share of the running sum
+};
+
+// bytes (0,1) or (2,3) of w as two floats; the selector folds to a constant after unrolling
+__device__ __forceinline__ f32x2 cvt2_fp8(uint32_t w, bool upper) {
+    return upper ? __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true) : __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
+}
+
+// four fp8 bytes of w -> two dwords of packed bf16 (exact)
+__device__ __forceinline__ void fp8x4_to_bf16x4(uint32_t w, uint32_t &d0, uint32_t &d1) {
+    const f32x2 a = cvt2_fp8(w, false), b = cvt2_fp8(w, true);
+    d0 = __builtin_amdgcn_perm(__float_as_uint(a[1]), __float_as_uint(a[0]), kSelHi);
+    d1 = __builtin_amdgcn_perm(__float_as_uint(b[1]), __float_as_uint(b[0]), kSelHi);
+}
+
+__device__ __forceinline__ uint32_t word(const uint4 &v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
+
+// S^T = K Q^T for one 32-key tile: s[rb][kblk] component r = key 16*kblk + 4q + r, row 16*rb + x
+template <int NR, int KVD>
+__device__ __forceinline__ void qk_tile(f32x4 (&s)[NR][2], const uint32_t (&qf)[NR][4][4], const TileK<KVD> &t) {
+#pragma unroll
+    for (int kblk = 0; kblk < 2; ++kblk) {
+        uint32_t kf[4][4];
+        if constexpr (KVD == MOSKA_BF16) {
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) kf[kb][i] = word(t.k[kblk][kb], i);
+        } else {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                fp8x4_to_bf16x4(t.k[kblk][u].x, kf[2 * u][0], kf[2 * u][1]);
+                fp8x4_to_bf16x4(t.k[kblk][u].y, kf[2 * u][2], kf[2 * u][3]);
+                fp8x4_to_bf16x4(t.k[kblk][u].z, kf[2 * u + 1][0], kf[2 * u + 1][1]);
+                fp8x4_to_bf16x4(t.k[kblk][u].w, kf[2 * u + 1][2], kf[2 * u + 1][3]);
+            }
+        }
+#pragma unroll
+        for (int rb = 0; rb < NR; ++rb) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) acc = mfma16(kf[kb], qf[rb][kb], acc);
+            s[rb][kblk] = acc;
+        }
+    }
+}
+
+// online softmax in the log2 domain; produces the P^T operands and rescales O when a max moved
+template <int NR, bool TAIL>
+__device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)[NR][2], uint32_t (&pf)[NR][4],
+                                             int key0, int nkeys, float sc, int q) {
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) {
+        float v[8];
+#pragma unroll
+        for (int kblk = 0; kblk < 2; ++kblk)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float z = s[rb][kblk][r] * sc;
+                if (TAIL && key0 + 16 * kblk + 4 * q + r >= nkeys) z = -INFINITY;   // rows past the end read as 0
+                v[4 * kblk + r] = z;
+            }
+        float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float mn = fmaxf(st.m[rb], mx);        // finite: every tile holds at least one real key
+        const float alpha = __builtin_amdgcn_exp2f(st.m[rb] - mn);
+        st.m[rb] = mn;
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            v[i] = __builtin_amdgcn_exp2f(v[i] - mn);
+            sum += v[i];
+        }
+        st.l[rb] = st.l[rb] * alpha + sum;
+        if (__any(alpha != 1.f)) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) st.o[rb][e] *= alpha;
+        }
+        pf[rb][0] = pack_bf16(v[0], v[1]);
+        pf[rb][1] = pack_bf16(v[2], v[3]);
+        pf[rb][2] = pack_bf16(v[4], v[5]);
+        pf[rb][3] = pack_bf16(v[6], v[7]);
+    }
+}
+
+// O^T += V^T P^T for one 32-key tile
+template <int NR, int KVD>
+__device__ __forceinline__ void pv_tile(WaveState<NR> &st, const TileV<KVD> &t, const uint32_t (&pf)[NR][4]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        uint32_t vf[4];
+#pragma unroll
+        for (int pr = 0; pr < 4; ++pr) {
+            if constexpr (KVD == MOSKA_BF16) {
+                vf[pr] = __builtin_amdgcn_perm(word(t.v[2 * pr + 1], e >> 1), word(t.v[2 * pr], e >> 1),
+                                               (e & 1) ? kSelHi : kSelLo);
+            } else {
+                const uint32_t wa = e < 4 ? t.v[2 * pr + 1].x : t.v[2 * pr + 1].y;
+                const uint32_t wb = e < 4 ? t.v[2 * pr].x : t.v[2 * pr].y;
+                const f32x2 fa = cvt2_fp8(wa, (e & 2) != 0), fb = cvt2_fp8(wb, (e & 2) != 0);
+                vf[pr] = __builtin_amdgcn_perm(__float_as_uint(fa[e & 1]), __float_as_uint(fb[e & 1]), kSelHi);
+            }
+        }
+#pragma unroll
+        for (int rb = 0; rb < NR; ++rb) st.o[rb][e] = mfma16(vf, pf[rb], st.o[rb][e]);
+    }
+}
+
+// Stream keys [0,nkeys) of one key set; wave `wave` of NW takes tiles wave, wave+NW, ...
+// One key tile and one value tile per wave are in flight: a tile's registers are refilled with
+// the wave's next tile as soon as the MFMAs that read them have issued (loads past the end of the
+// set are dropped by the range check, so the refill needs no branch).  Latency is hidden by the
+// other waves of the SIMD.
+template <int NR, int KVD, int NW>
+__device__ __forceinline__ void attend(WaveState<NR> &st, const uint32_t (&qf)[NR][4][4], const char *Kb,
+                                       const char *Vb, int nkeys, float sc, int wave, int q, int x) {
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) {
+        st.m[rb] = -INFINITY;
+        st.l[rb] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st.o[rb][e] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const int nfull = nkeys >> 5;                  // tiles without a ragged end
+    const LaneOff<KVD> lo(q, x);
+    const __amdgpu_buffer_rsrc_t rk = key_set_rsrc(Kb, (uint32_t)nkeys * row_bytes<KVD>());
+    const __amdgpu_buffer_rsrc_t rv = key_set_rsrc(Vb, (uint32_t)nkeys * row_bytes<KVD>());
+    TileK<KVD> tk;
+    TileV<KVD> tv;
+    f32x4 s[NR][2];
+    uint32_t pf[NR][4];
+    int t = wave;
+    if (t < nfull) {
+        load_k<KVD>(tk, rk, lo, t);
+        load_v<KVD>(tv, rv, lo, t);
+        do {
+            qk_tile<NR, KVD>(s, qf, tk);
+            load_k<KVD>(tk, rk, lo, t + NW);
+            softmax_tile<NR, false>(st, s, pf, 32 * t, nkeys, sc, q);
+            pv_tile<NR, KVD>(st, tv, pf);
+            load_v<KVD>(tv, rv, lo, t + NW);
+            t += NW;
+        } while (t < nfull);
+    }
+    if ((nkeys & 31) && (nfull % NW) == wave) {    // the ragged last tile belongs to one wave
+        load_k<KVD>(tk, rk, lo, nfull);
+        load_v<KVD>(tv, rv, lo, nfull);
+        qk_tile<NR, KVD>(s, qf, tk);
+        softmax_tile<NR, true>(st, s, pf, 32 * nfull, nkeys, sc, q);
+        pv_tile<NR, KVD>(st, tv, pf);
+    }
+}
+
+// Merge the NW waves' states pairwise through LDS and let wave 0 write the rows.
+// orow[rb]: index of row 16rb+x in part_LSE (part_O row = orow*HD), or -1 for a padding row.
+template <int NR, int NW>
+__device__ __forceinline__ void combine_and_store(WaveState<NR> &st, float *lds, int wave, int q, int x,
+                                                  const int64_t (&orow)[NR], float vmul, float *part_O,
+                                                  float *part_LSE) {
+    constexpr int R = 16 * NR;
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) {
+        float l = st.l[rb];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        st.l[rb] = l;
+    }
+#pragma unroll
+    for (int s = NW / 2; s >= 1; s >>= 1) {
+        if (wave >= s && wave < 2 * s) {
+            float *buf = lds + (size_t)(wave - s) * R * OSTRIDE;
+#pragma unroll
+            for (int rb = 0; rb < NR; ++rb) {
+                float *row = buf + (16 * rb + x) * OSTRIDE;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) row[32 * q + 8 * r + e] = st.o[rb][e][r];
+                if (q == 0) {
+                    row[HD] = st.m[rb];
+                    row[HD + 1] = st.l[rb];
+                }
+            }
+        }
+        __syncthreads();
+        if (wave < s) {
+            const float *buf = lds + (size_t)wave * R * OSTRIDE;
+#pragma unroll
+            for (int rb = 0; rb < NR; ++rb) {
+                const float *row = buf + (16 * rb + x) * OSTRIDE;
+                const float m2 = row[HD], l2 = row[HD + 1];
+                const float mn = fmaxf(st.m[rb], m2);
+                const float a1 = st.m[rb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(st.m[rb] - mn);
+                const float a2 = m2 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m2 - mn);
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) st.o[rb][e][r] = st.o[rb][e][r] * a1 + row[32 * q + 8 * r + e] * a2;
+                st.l[rb] = st.l[rb] * a1 + l2 * a2;
+                st.m[rb] = mn;
+            }
+        }
+        __syncthreads();
+    }
+    if (wave == 0) {
+#pragma unroll
+        for (int rb = 0; rb < NR; ++rb) {
+            if (orow[rb] < 0) continue;
+            const float l = st.l[rb];
+            const float inv = l > 0.f ? vmul / l : 0.f;
+            float *o = part_O + orow[rb] * HD + 32 * q;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float4 lo = {st.o[rb][0][r] * inv, st.o[rb][1][r] * inv, st.o[rb][2][r] * inv, st.o[rb][3][r] * inv};
+                const float4 hi = {st.o[rb][4][r] * inv, st.o[rb][5][r] * inv, st.o[rb][6][r] * inv, st.o[rb][7][r] * inv};
+                *(float4 *)(o + 8 * r) = lo;
+                *(float4 *)(o + 8 * r + 4) = hi;
+            }
+            if (q == 0) part_LSE[orow[rb]] = l > 0.f ? (st.m[rb] + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+        }
+    }
+}
+
+// Q^T operand of a row (element offset qoff into Q, or zeros for a padding row)
+template <int KVD>
+__device__ __forceinline__ void load_q(uint32_t (&qf)[4][4], const void *Q, int64_t qoff, bool valid, int q) {
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+        uint4 v = {0u, 0u, 0u, 0u};
+        if (valid) v = *(const uint4 *)((const uint16_t *)Q + qoff + qk_dim0<KVD>(kb, q));
+        qf[kb][0] = v.x; qf[kb][1] = v.y; qf[kb][2] = v.z; qf[kb][3] = v.w;
+    }
+}
+
+// Up to 32 rows fit in 256 registers per lane: asking for two waves per SIMD keeps the MFMA
+// accumulators in architectural VGPRs, where the softmax rescale can touch them without copies.
+constexpr int min_waves(int NR) { return NR == 1 ? 3 : NR == 2 ? 2 : 1; }
+
+template <int NR, int KVD, int NW>
+__global__ __launch_bounds__(NW * 64, min_waves(NR)) void shared_mfma_kernel(SharedArgs a, int Hq, int Hkv, int C, int L, int k,
+                                                               float scale) {
+    __shared__ float comb[(NW / 2) * 16 * NR * OSTRIDE];
+    // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of the
+    // tile list so the tiles of one bucket (which re-read the same chunk) share an L2.
+    const int ntiles = a.tile_hdr[0];
+    const int per = (ntiles + 7) >> 3, slot = blockIdx.x >> 3;
+    const int w = (blockIdx.x & 7) * per + slot;
+    if (slot >= per || w >= ntiles) return;
+    const int bkt = a.tiles[2 * w], row0 = a.tiles[2 * w + 1];
+    const int h = bkt / C, c = bkt - h * C, G = Hq / Hkv;
+    const int beg = a.off[bkt], rows = (a.off[bkt + 1] - beg) * G;
+    const int lane = threadIdx.x & 63, q = lane >> 4, x = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps tile indices in SGPRs
+
+    uint32_t qf[NR][4][4];
+    int64_t orow[NR];
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) {
+        const int rr = row0 + 16 * rb + x;
+        const bool valid = rr < rows;
+        int64_t qoff = 0;
+        orow[rb] = -1;
+        if (valid) {
+            const int item = a.items[beg + rr / G], g = rr % G;
+            const int b = item / k, j = item - b * k;
+            const int64_t bh = (int64_t)b * Hq + h * G + g;
+            qoff = bh * HD;
+            orow[rb] = bh * (k + 1) + j;
+        }
+        load_q<KVD>(qf[rb], a.Q, qoff, valid, q);
+    }
+    const float kmul = a.scale_k ? a.scale_k[c * Hkv + h] : 1.f;
+    const float vmul = a.scale_v ? a.scale_v[c * Hkv + h] : 1.f;
+    const int64_t base = ((int64_t)c * Hkv + h) * L * row_bytes<KVD>();
+    WaveState<NR> st;
+    attend<NR, KVD, NW>(st, qf, (const char *)a.Ks + base, (const char *)a.Vs + base, L,
+                                  scale * kmul * kLog2e, wave, q, x);
+    combine_and_store<NR, NW>(st, comb, wave, q, x, orow, vmul, a.part_O, a.part_LSE);
+}
+
+template <int NR, int NW>
+__global__ __launch_bounds__(NW * 64, min_waves(NR)) void unique_mfma_kernel(UniqueArgs a, int Hq, int Hkv, int U, int k,
+                                                               float scale) {
+    __shared__ float comb[(NW / 2) * 16 * NR * OSTRIDE];
+    const int G = Hq / Hkv, gt = (G + 16 * NR - 1) / (16 * NR);
+    const int bh = blockIdx.x / gt, g0 = (blockIdx.x % gt) * 16 * NR;
+    const int b = bh / Hkv, h = bh - b * Hkv;
+    const int lane = threadIdx.x & 63, q = lane >> 4, x = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps tile indices in SGPRs
+    uint32_t qf[NR][4][4];
+    int64_t orow[NR];
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) {
+        const int g = g0 + 16 * rb + x;
+        const bool valid = g < G;
+        const int64_t row = (int64_t)b * Hq + h * G + (valid ? g : 0);
+        orow[rb] = valid ? row * (k + 1) + k : -1;
+        load_q<MOSKA_BF16>(qf[rb], a.Q, row * HD, valid, q);
+    }
+    const int nkeys = a.unique_len ? min(max(a.unique_len[b], 0), U) : U;
+    const int64_t base = ((int64_t)b * Hkv + h) * U * row_bytes<MOSKA_BF16>();
+    WaveState<NR> st;
+    attend<NR, MOSKA_BF16, NW>(st, qf, (const char *)a.Ku + base, (const char *)a.Vu + base, nkeys,
+                                         scale * kLog2e, wave, q, x);
+    combine_and_store<NR, NW>(st, comb, wave, q, x, orow, 1.f, a.part_O, a.part_LSE);
+}
+
+// Tuning variant of a kernel instantiation: row blocks and waves per workgroup.
+struct Variant { int NR, NW; };
+
+}  // namespace mfma
+}  // namespace moska
