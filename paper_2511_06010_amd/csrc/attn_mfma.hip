@@ -19,11 +19,11 @@ int launch_unique_mfma(const moska_problem_t &p, const UniqueArgs &a, hipStream_
         Variant v;
         const void *kernel;
     };
-#define MOSKA_UV(NR, NW) \
-    UniqueVariant { Variant{NR, NW}, (const void *)unique_mfma_kernel<NR, NW> }
+#define MOSKA_UV(NR, NW, AUX, NKB) \
+    UniqueVariant { Variant{NR, NW, AUX, NKB}, (const void *)unique_mfma_kernel<NR, NW, AUX, NKB> }
     // first entry of each row count is the default; MOSKA_UNIQUE_VARIANT=<index> picks another
     static const UniqueVariant table[] = {
-        MOSKA_UV(1, 4), MOSKA_UV(1, 8), MOSKA_UV(1, 2), MOSKA_UV(2, 4), MOSKA_UV(4, 4),
+        MOSKA_UV(1, 4, 2, 1), MOSKA_UV(1, 4, 2, 2), MOSKA_UV(1, 8, 2, 1), MOSKA_UV(2, 4, 2, 1), MOSKA_UV(4, 4, 2, 2),
     };
 #undef MOSKA_UV
     const int G = p.Hq / p.Hkv;

@@ -16,12 +16,13 @@ struct SharedVariant {
 
 template <int KVD>
 int launch_shared_variant(const moska_problem_t &p, const SharedArgs &a, int MT, hipStream_t s) {
-#define MOSKA_SV(NR, NW) \
-    SharedVariant { Variant{NR, NW}, (const void *)shared_mfma_kernel<NR, KVD, NW> }
+#define MOSKA_SV(NR, NW, AUX, NKB) \
+    SharedVariant { Variant{NR, NW, AUX, NKB}, (const void *)shared_mfma_kernel<NR, KVD, NW, AUX, NKB> }
     // first entry of each row count is the default; the others are reachable through
     // MOSKA_SHARED_VARIANT=<index within that row count> for tuning runs
     static const SharedVariant table[] = {
-        MOSKA_SV(1, 4), MOSKA_SV(1, 8), MOSKA_SV(2, 4), MOSKA_SV(2, 8), MOSKA_SV(4, 4),
+        MOSKA_SV(1, 4, 0, 1), MOSKA_SV(1, 4, 2, 1), MOSKA_SV(2, 4, 0, 1), MOSKA_SV(2, 4, 2, 1), MOSKA_SV(2, 4, 2, 2),
+        MOSKA_SV(4, 4, 2, 2), MOSKA_SV(4, 4, 2, 1), MOSKA_SV(4, 4, 0, 2),
     };
 #undef MOSKA_SV
     const int NR = MT / 16;
