@@ -14,17 +14,16 @@ bool use_mfma_path(const moska_problem_t &p) {
     return !force_generic && p.q_dtype == MOSKA_BF16 && p.D == 128;
 }
 
-int shared_tile_rows(const moska_problem_t &p) {
-    if (!use_mfma_path(p)) return 16;
-    if (const char *e = std::getenv("MOSKA_SHARED_MT")) {   // tuning override: 16, 32 or 64
-        const int mt = std::atoi(e);
-        if (mt == 16 || mt == 32 || mt == 64) return mt;
-    }
-    // mean rows per bucket; a tile should hold a typical bucket so its chunk is streamed once
-    const double mean = (double)p.B * p.k * (p.Hq / p.Hkv) / p.C;
-    if (mean <= 12.0) return 16;
-    if (mean <= 24.0) return 32;
-    return 64;
+SharedPlan shared_plan(const moska_problem_t &p) {
+    if (!use_mfma_path(p)) return SharedPlan{0, 0};          // the vector-ALU kernel serves 16-row tiles
+    SharedPlan pl{0, kNumClasses - 1};
+    // tuning overrides: smallest / largest tile class (0..4 = 16, 32, 64, 128, 256 rows)
+    if (const char *e = std::getenv("MOSKA_SHARED_CMIN")) pl.cmin = std::atoi(e);
+    if (const char *e = std::getenv("MOSKA_SHARED_CMAX")) pl.cmax = std::atoi(e);
+    if (pl.cmin < 0) pl.cmin = 0;
+    if (pl.cmax > kNumClasses - 1) pl.cmax = kNumClasses - 1;
+    if (pl.cmin > pl.cmax) pl.cmin = pl.cmax;
+    return pl;
 }
 
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -32,10 +31,11 @@ static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 Workspace carve_workspace(const moska_problem_t &p, void *ws) {
     Workspace w;
     const size_t items = (size_t)p.B * p.Hkv * p.k, nb = (size_t)p.Hkv * p.C;
-    const size_t tmax = (size_t)max_tiles(p, 16);          // bound valid for every tile size >= 16
+    // bound valid for every plan: at most one remainder tile per class and bucket plus the full tiles
+    const size_t tmax = (size_t)(4 * (items < nb ? items : nb) + (items * (size_t)(p.Hq / p.Hkv)) / 16 + 8);
     char *base = (char *)ws;
     size_t o = 0;
-    w.tile_hdr = (int32_t *)(base + o); o += align_up(4 * sizeof(int32_t));
+    w.tile_hdr = (int32_t *)(base + o); o += align_up(8 * sizeof(int32_t));
     w.tiles = (int32_t *)(base + o);    o += align_up(2 * tmax * sizeof(int32_t));
     w.rank = (int32_t *)(base + o);     o += align_up(items * sizeof(int32_t));
     w.off = (int32_t *)(base + o);      o += align_up((nb + 1) * sizeof(int32_t));
@@ -121,10 +121,10 @@ int moska_shared_attn(const moska_problem_t *p, const void *Q, const void *Ks, c
         bucket_off = w.off;
         bucket_items = w.items;
     }
-    const int MT = shared_tile_rows(*p);
-    if (int rc = launch_tile_list(*p, bucket_off, MT, w.tile_hdr, w.tiles, s)) return rc;
+    const SharedPlan pl = shared_plan(*p);
+    if (int rc = launch_tile_list(*p, bucket_off, pl, w.tile_hdr, w.tiles, s)) return rc;
     SharedArgs a{Q, Ks, Vs, scale_k, scale_v, bucket_off, bucket_items, w.tile_hdr, w.tiles, part_O, part_LSE};
-    return use_mfma_path(*p) ? launch_shared_mfma(*p, a, MT, s) : launch_shared_generic(*p, a, MT, s);
+    return use_mfma_path(*p) ? launch_shared_mfma(*p, a, pl, s) : launch_shared_generic(*p, a, pl, s);
 }
 
 int moska_unique_attn(const moska_problem_t *p, const void *Q, const void *Ku, const void *Vu,

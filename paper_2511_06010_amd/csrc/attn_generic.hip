@@ -106,9 +106,10 @@ __device__ void attend_tile_rows(const RowSet &rs, const int64_t *q_off, const i
 
 template <int QD, int KD>
 __global__ __launch_bounds__(256) void shared_generic_kernel(SharedArgs a, int B, int Hq, int Hkv, int D, int C,
-                                                              int L, int k, float scale, int MT) {
+                                                              int L, int k, float scale) {
     __shared__ int64_t q_off[TR], o_row[TR];
-    const int ntiles = a.tile_hdr[0];
+    constexpr int MT = TR;
+    const int ntiles = a.tile_hdr[1] - a.tile_hdr[0];    // only the 16-row class is in use
     if ((int)blockIdx.x >= ntiles) return;
     const int bkt = a.tiles[2 * blockIdx.x], row0 = a.tiles[2 * blockIdx.x + 1];
     const int h = bkt / C, c = bkt - h * C, G = Hq / Hkv, P = k + 1;
@@ -161,18 +162,18 @@ int set_lds(Kern kern, size_t lds) {
 
 }  // namespace
 
-int launch_shared_generic(const moska_problem_t &p, const SharedArgs &a, int MT, hipStream_t s) {
-    if (MT != TR) return MOSKA_ERR_UNSUPPORTED;
+int launch_shared_generic(const moska_problem_t &p, const SharedArgs &a, const SharedPlan &pl, hipStream_t s) {
+    if (pl.cmin != 0 || pl.cmax != 0 || class_rows(0) != TR) return MOSKA_ERR_UNSUPPORTED;
     const size_t lds = generic_lds_bytes(p.D);
-    const unsigned grid = (unsigned)max_tiles(p, MT);
+    const unsigned grid = (unsigned)class_bound(p, pl, 0);
     if (grid == 0) return MOSKA_OK;
-    void (*kern)(SharedArgs, int, int, int, int, int, int, int, float, int) = nullptr;
+    void (*kern)(SharedArgs, int, int, int, int, int, int, int, float) = nullptr;
     if (p.q_dtype == MOSKA_F32 && p.shared_kv_dtype == MOSKA_F32) kern = shared_generic_kernel<MOSKA_F32, MOSKA_F32>;
     else if (p.q_dtype == MOSKA_BF16 && p.shared_kv_dtype == MOSKA_BF16) kern = shared_generic_kernel<MOSKA_BF16, MOSKA_BF16>;
     else if (p.q_dtype == MOSKA_BF16 && p.shared_kv_dtype == MOSKA_FP8_E4M3) kern = shared_generic_kernel<MOSKA_BF16, MOSKA_FP8_E4M3>;
     else return MOSKA_ERR_UNSUPPORTED;
     if (int rc = set_lds(kern, lds)) return rc;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, a, p.B, p.Hq, p.Hkv, p.D, p.C, p.L, p.k, p.scale, MT);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, a, p.B, p.Hq, p.Hkv, p.D, p.C, p.L, p.k, p.scale);
     return hip_status(hipGetLastError());
 }
 

@@ -292,8 +292,29 @@ __device__ __forceinline__ void attend(WaveState<NR> &st, const uint32_t (&qf)[N
     }
 }
 
-// Merge the NW waves' states pairwise through LDS and let wave 0 write the rows.
+// Normalise and write the rows a wave holds (st.l already summed over the row's four lanes).
 // orow[rb]: index of row 16rb+x in part_LSE (part_O row = orow*HD), or -1 for a padding row.
+template <int NR>
+__device__ __forceinline__ void store_rows(const WaveState<NR> &st, int q, const int64_t (&orow)[NR], float vmul,
+                                           float *part_O, float *part_LSE) {
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) {
+        if (orow[rb] < 0) continue;
+        const float l = st.l[rb];
+        const float inv = l > 0.f ? vmul / l : 0.f;
+        float *o = part_O + orow[rb] * HD + 32 * q;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float4 lo = {st.o[rb][0][r] * inv, st.o[rb][1][r] * inv, st.o[rb][2][r] * inv, st.o[rb][3][r] * inv};
+            const float4 hi = {st.o[rb][4][r] * inv, st.o[rb][5][r] * inv, st.o[rb][6][r] * inv, st.o[rb][7][r] * inv};
+            *(float4 *)(o + 8 * r) = lo;
+            *(float4 *)(o + 8 * r + 4) = hi;
+        }
+        if (q == 0) part_LSE[orow[rb]] = l > 0.f ? (st.m[rb] + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+    }
+}
+
+// Merge the NW waves' states pairwise through LDS and let wave 0 write the rows.
 template <int NR, int NW>
 __device__ __forceinline__ void combine_and_store(WaveState<NR> &st, float *lds, int wave, int q, int x,
                                                   const int64_t (&orow)[NR], float vmul, float *part_O,
@@ -343,23 +364,7 @@ __device__ __forceinline__ void combine_and_store(WaveState<NR> &st, float *lds,
         }
         __syncthreads();
     }
-    if (wave == 0) {
-#pragma unroll
-        for (int rb = 0; rb < NR; ++rb) {
-            if (orow[rb] < 0) continue;
-            const float l = st.l[rb];
-            const float inv = l > 0.f ? vmul / l : 0.f;
-            float *o = part_O + orow[rb] * HD + 32 * q;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float4 lo = {st.o[rb][0][r] * inv, st.o[rb][1][r] * inv, st.o[rb][2][r] * inv, st.o[rb][3][r] * inv};
-                const float4 hi = {st.o[rb][4][r] * inv, st.o[rb][5][r] * inv, st.o[rb][6][r] * inv, st.o[rb][7][r] * inv};
-                *(float4 *)(o + 8 * r) = lo;
-                *(float4 *)(o + 8 * r + 4) = hi;
-            }
-            if (q == 0) part_LSE[orow[rb]] = l > 0.f ? (st.m[rb] + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
-        }
-    }
+    if (wave == 0) store_rows<NR>(st, q, orow, vmul, part_O, part_LSE);
 }
 
 // Q^T operand of a row (element offset qoff into Q, or zeros for a padding row)
@@ -373,21 +378,11 @@ __device__ __forceinline__ void load_q(uint32_t (&qf)[4][4], const void *Q, int6
     }
 }
 
-// Up to 32 rows fit in 256 registers per lane: asking for two waves per SIMD keeps the MFMA
-// accumulators in architectural VGPRs, where the softmax rescale can touch them without copies.
-constexpr int min_waves(int NR) { return NR == 1 ? 3 : NR == 2 ? 2 : 1; }
-
+// Tile (bkt, row0) of Shared KV Attention on the streaming path: up to 16*NR gathered rows of
+// bucket bkt against its chunk.  comb: LDS for the cross-wave merge, (NW/2)*16*NR*OSTRIDE floats.
 template <int NR, int KVD, int NW, int AUX, int NKB>
-__global__ __launch_bounds__(NW * 64, min_waves(NR)) void shared_mfma_kernel(SharedArgs a, int Hq, int Hkv, int C, int L, int k,
-                                                               float scale) {
-    __shared__ float comb[(NW / 2) * 16 * NR * OSTRIDE];
-    // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of the
-    // tile list so the tiles of one bucket (which re-read the same chunk) share an L2.
-    const int ntiles = a.tile_hdr[0];
-    const int per = (ntiles + 7) >> 3, slot = blockIdx.x >> 3;
-    const int w = (blockIdx.x & 7) * per + slot;
-    if (slot >= per || w >= ntiles) return;
-    const int bkt = a.tiles[2 * w], row0 = a.tiles[2 * w + 1];
+__device__ __forceinline__ void stream_tile(const SharedArgs &a, int bkt, int row0, int Hq, int Hkv, int C, int L,
+                                            int k, float scale, float *comb) {
     const int h = bkt / C, c = bkt - h * C, G = Hq / Hkv;
     const int beg = a.off[bkt], rows = (a.off[bkt + 1] - beg) * G;
     const int lane = threadIdx.x & 63, q = lane >> 4, x = lane & 15;
@@ -417,6 +412,31 @@ __global__ __launch_bounds__(NW * 64, min_waves(NR)) void shared_mfma_kernel(Sha
     attend<NR, KVD, NW, AUX, NKB>(st, qf, (const char *)a.Ks + base, (const char *)a.Vs + base, L,
                                   scale * kmul * kLog2e, wave, q, x);
     combine_and_store<NR, NW>(st, comb, wave, q, x, orow, vmul, a.part_O, a.part_LSE);
+}
+
+// Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of the tile
+// list so the tiles of one bucket (which re-read the same chunk) share an L2.  Returns the tile
+// index inside [0, ntiles) or -1 if this workgroup has none.
+__device__ __forceinline__ int xcd_tile_index(int ntiles) {
+    const int per = (ntiles + 7) >> 3, slot = blockIdx.x >> 3;
+    const int w = (blockIdx.x & 7) * per + slot;
+    return (slot >= per || w >= ntiles) ? -1 : w;
+}
+
+// Up to 32 rows fit in 256 registers per lane: asking for two waves per SIMD keeps the MFMA
+// accumulators in architectural VGPRs, where the softmax rescale can touch them without copies.
+constexpr int min_waves(int NR) { return NR == 1 ? 3 : NR == 2 ? 2 : 1; }
+
+// One size class of the tile list, streaming path.
+template <int NR, int KVD, int NW, int AUX, int NKB>
+__global__ __launch_bounds__(NW * 64, min_waves(NR)) void shared_mfma_kernel(SharedArgs a, int cls, int Hq, int Hkv,
+                                                                              int C, int L, int k, float scale) {
+    __shared__ float comb[(NW / 2) * 16 * NR * OSTRIDE];
+    const int first = a.tile_hdr[cls];
+    const int w = xcd_tile_index(a.tile_hdr[cls + 1] - first);
+    if (w < 0) return;
+    stream_tile<NR, KVD, NW, AUX, NKB>(a, a.tiles[2 * (first + w)], a.tiles[2 * (first + w) + 1], Hq, Hkv, C, L, k,
+                                       scale, comb);
 }
 
 template <int NR, int NW, int AUX, int NKB>

@@ -5,12 +5,12 @@
 
 namespace moska {
 
-int launch_shared_mfma_bf16(const moska_problem_t &p, const SharedArgs &a, int MT, hipStream_t s);
-int launch_shared_mfma_fp8(const moska_problem_t &p, const SharedArgs &a, int MT, hipStream_t s);
+int launch_shared_mfma_bf16(const moska_problem_t &p, const SharedArgs &a, const SharedPlan &pl, hipStream_t s);
+int launch_shared_mfma_fp8(const moska_problem_t &p, const SharedArgs &a, const SharedPlan &pl, hipStream_t s);
 
-int launch_shared_mfma(const moska_problem_t &p, const SharedArgs &a, int MT, hipStream_t s) {
-    return p.shared_kv_dtype == MOSKA_FP8_E4M3 ? launch_shared_mfma_fp8(p, a, MT, s)
-                                               : launch_shared_mfma_bf16(p, a, MT, s);
+int launch_shared_mfma(const moska_problem_t &p, const SharedArgs &a, const SharedPlan &pl, hipStream_t s) {
+    return p.shared_kv_dtype == MOSKA_FP8_E4M3 ? launch_shared_mfma_fp8(p, a, pl, s)
+                                               : launch_shared_mfma_bf16(p, a, pl, s);
 }
 
 int launch_unique_mfma(const moska_problem_t &p, const UniqueArgs &a, hipStream_t s) {

@@ -1,0 +1,234 @@
+// Shared KV Attention for large buckets (64, 128 or 256 query rows per tile), paper Sec. III-A:
+// the regime where batching the queries of a chunk turns the chunk's K/V stream into a GEMM.
+//
+// A workgroup of NWV waves owns 16*NR*NWV rows of one bucket; each wave owns 16*NR of them for
+// ALL keys of the chunk, so no cross-wave merge is needed.  The chunk's K and V are streamed
+// from HBM once per workgroup: every thread fetches a slice of the next 32-key stage into
+// registers while the current stage is consumed from LDS, then writes its slice to the other
+// LDS buffer (an fp8 store is widened to bf16 here, once per workgroup instead of once per
+// wave).  One barrier per stage.
+//
+// LDS stage layout (bf16): K[32 keys][256 B] with the 16-byte units of a row XOR-swizzled by
+// (key & 15), so the MFMA A-operand read (16 keys x one unit, 16 lanes per phase) is free of bank
+// conflicts; V[32 keys][256 B] plain (its reads take whole rows).  The waves read operands in
+// the same lane layout as the streaming kernels (attn_mfma.h) and reuse their MFMA / softmax
+// code.
+#pragma once
+
+#include "attn_mfma.h"
+
+namespace moska {
+namespace mfma {
+
+// One thread's slice of a KT-key stage in registers (T threads per workgroup).
+template <int KVD, int T, int KT> struct StageRegs {
+    // 16-byte units of K (and of V) per thread; a unit of fp8 becomes two units of bf16 in LDS
+    static constexpr int N = (KT * (KVD == MOSKA_BF16 ? 16 : 8)) / T;
+    static_assert(N >= 1, "stage too small for the workgroup");
+    uint4 k[N], v[N];
+};
+
+template <int KVD, int T, int KT, int AUX>
+__device__ __forceinline__ void stage_fetch(StageRegs<KVD, T, KT> &r, __amdgpu_buffer_rsrc_t rk,
+                                            __amdgpu_buffer_rsrc_t rv, int stage, int tid) {
+    constexpr int ROWB = row_bytes<KVD>();
+    constexpr int N = StageRegs<KVD, T, KT>::N;
+    const uint32_t off = (uint32_t)stage * (KT * ROWB) + (uint32_t)tid * 16u;   // consecutive threads, consecutive units
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        r.k[i] = as_uint4(__builtin_amdgcn_raw_buffer_load_b128(rk, off + i * T * 16, 0, AUX));
+        r.v[i] = as_uint4(__builtin_amdgcn_raw_buffer_load_b128(rv, off + i * T * 16, 0, AUX));
+    }
+}
+
+__device__ __forceinline__ void fp8x16_to_bf16(const uint4 &w, uint4 &lo, uint4 &hi) {
+    fp8x4_to_bf16x4(w.x, lo.x, lo.y);
+    fp8x4_to_bf16x4(w.y, lo.z, lo.w);
+    fp8x4_to_bf16x4(w.z, hi.x, hi.y);
+    fp8x4_to_bf16x4(w.w, hi.z, hi.w);
+}
+
+// lk, lv: one LDS buffer's K and V areas (KT*16 uint4 each)
+template <int KVD, int T, int KT>
+__device__ __forceinline__ void stage_store(const StageRegs<KVD, T, KT> &r, uint4 *lk, uint4 *lv, int tid) {
+    constexpr int N = StageRegs<KVD, T, KT>::N;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int g = tid + i * T;
+        if constexpr (KVD == MOSKA_BF16) {
+            const int row = g >> 4, u = g & 15;
+            lk[row * 16 + (u ^ (row & 15))] = r.k[i];
+            lv[g] = r.v[i];
+        } else {
+            const int row = g >> 3, u = (g & 7) * 2;       // 8 fp8 units per key row -> bf16 units u, u+1
+            uint4 lo, hi;
+            fp8x16_to_bf16(r.k[i], lo, hi);
+            lk[row * 16 + (u ^ (row & 15))] = lo;
+            lk[row * 16 + ((u + 1) ^ (row & 15))] = hi;
+            fp8x16_to_bf16(r.v[i], lo, hi);
+            lv[row * 16 + u] = lo;
+            lv[row * 16 + u + 1] = hi;
+        }
+    }
+}
+
+// MFMA operands of one 32-key sub-tile out of LDS, in the register layout of the streaming kernels
+__device__ __forceinline__ void stage_read_k(TileK<MOSKA_BF16> &t, const uint4 *lk, int q, int x) {
+#pragma unroll
+    for (int kblk = 0; kblk < 2; ++kblk)
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) t.k[kblk][kb] = lk[(16 * kblk + x) * 16 + ((4 * kb + q) ^ x)];
+}
+__device__ __forceinline__ void stage_read_v(TileV<MOSKA_BF16> &t, const uint4 *lv, int q, int x) {
+#pragma unroll
+    for (int s = 0; s < 8; ++s) t.v[s] = lv[(4 * q + slot_row(s)) * 16 + x];
+}
+
+// LDS footprint of a tile kernel, in uint4 units: two buffers of K and V stages
+template <int KT> constexpr int lds_units() { return 4 * KT * 16; }
+
+// Tile (bkt, row0) on the LDS-staged path: 16*NR*NWV rows.  smem: lds_units<KT>() uint4.
+// KT keys per stage (32 or 64); PD stages of global loads are kept in flight in registers (2 or 4):
+// the loads of stage t+1+PD are issued when stage t+1 has been copied to LDS, so they have PD
+// stages of MFMA work to land.
+template <int NR, int NWV, int KVD, int AUX, int KT, int PD>
+__device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0, int Hq, int Hkv, int C, int L, int k,
+                                         float scale, uint4 *smem) {
+    static_assert(KT == 32 || KT == 64, "keys per stage");
+    static_assert(PD == 1 || PD == 2 || PD == 4, "stages in flight");
+    constexpr int T = NWV * 64;
+    constexpr int SU = KT * 16;                            // uint4 units of K (or V) per stage
+    uint4 *ldsK = smem, *ldsV = smem + 2 * SU;
+    const int h = bkt / C, c = bkt - h * C, G = Hq / Hkv;
+    const int beg = a.off[bkt], rows = (a.off[bkt + 1] - beg) * G;
+    const int tid = threadIdx.x, lane = tid & 63, q = lane >> 4, x = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    uint32_t qf[NR][4][4];
+    int64_t orow[NR];
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) {
+        const int rr = row0 + (wave * NR + rb) * 16 + x;
+        const bool valid = rr < rows;
+        int64_t qoff = 0;
+        orow[rb] = -1;
+        if (valid) {
+            const int item = a.items[beg + rr / G], g = rr % G;
+            const int b = item / k, j = item - b * k;
+            const int64_t bh = (int64_t)b * Hq + h * G + g;
+            qoff = bh * HD;
+            orow[rb] = bh * (k + 1) + j;
+        }
+        load_q<MOSKA_BF16>(qf[rb], a.Q, qoff, valid, q);    // keys sit in LDS as bf16 in natural dim order
+    }
+    const float kmul = a.scale_k ? a.scale_k[c * Hkv + h] : 1.f;
+    const float vmul = a.scale_v ? a.scale_v[c * Hkv + h] : 1.f;
+    const float sc = scale * kmul * kLog2e;
+    const int64_t base = ((int64_t)c * Hkv + h) * L * row_bytes<KVD>();
+    const __amdgpu_buffer_rsrc_t rk = key_set_rsrc((const char *)a.Ks + base, (uint32_t)L * row_bytes<KVD>());
+    const __amdgpu_buffer_rsrc_t rv = key_set_rsrc((const char *)a.Vs + base, (uint32_t)L * row_bytes<KVD>());
+
+    WaveState<NR> st;
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) {
+        st.m[rb] = -INFINITY;
+        st.l[rb] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st.o[rb][e] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const int nst = (L + KT - 1) / KT;                     // stages; rows past L read as zeros
+    StageRegs<KVD, T, KT> regs[PD];                        // PD >= 2: regs[(t+1+j) % PD] carries stage t+1+j at step t
+    // stage t out of LDS buffer `cur`: scores, softmax, output for its 32-key sub-tiles
+    auto consume = [&](int t, int cur) {
+#pragma unroll
+        for (int sub = 0; sub < KT / 32; ++sub) {
+            TileK<MOSKA_BF16> tk;
+            TileV<MOSKA_BF16> tv;
+            f32x4 s[NR][2];
+            uint32_t pf[NR][4];
+            const int key0 = KT * t + 32 * sub;
+            stage_read_k(tk, ldsK + cur * SU + sub * 512, q, x);
+            qk_tile<NR, MOSKA_BF16>(s, qf, tk);
+            if (key0 + 32 > L) softmax_tile<NR, true>(st, s, pf, key0, L, sc, q);
+            else softmax_tile<NR, false>(st, s, pf, key0, L, sc, q);
+            stage_read_v(tv, ldsV + cur * SU + sub * 512, q, x);
+            pv_tile<NR, MOSKA_BF16>(st, tv, pf);
+        }
+    };
+    stage_fetch<KVD, T, KT, AUX>(regs[0], rk, rv, 0, tid);
+    stage_store<KVD, T, KT>(regs[0], ldsK, ldsV, tid);
+    if constexpr (PD == 1) {
+        __syncthreads();
+        for (int t = 0; t < nst; ++t) {
+            const int cur = t & 1;
+            stage_fetch<KVD, T, KT, AUX>(regs[0], rk, rv, t + 1, tid);   // past the end: dropped by the range check
+            consume(t, cur);
+            stage_store<KVD, T, KT>(regs[0], ldsK + (cur ^ 1) * SU, ldsV + (cur ^ 1) * SU, tid);
+            __syncthreads();
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < PD; ++j) stage_fetch<KVD, T, KT, AUX>(regs[(1 + j) % PD], rk, rv, 1 + j, tid);
+        __syncthreads();
+        for (int t0 = 0; t0 < nst; t0 += PD) {
+#pragma unroll
+            for (int u = 0; u < PD; ++u) {                 // unrolled: buffer and register indices are constants
+                const int t = t0 + u;
+                if (t < nst) {
+                    consume(t, u & 1);
+                    StageRegs<KVD, T, KT> &nx = regs[(u + 1) % PD];   // the registers that carry stage t+1
+                    stage_store<KVD, T, KT>(nx, ldsK + ((u + 1) & 1) * SU, ldsV + ((u + 1) & 1) * SU, tid);
+                    stage_fetch<KVD, T, KT, AUX>(nx, rk, rv, t + 1 + PD, tid);
+                    __syncthreads();
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) {
+        float l = st.l[rb];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        st.l[rb] = l;
+    }
+    store_rows<NR>(st, q, orow, vmul, a.part_O, a.part_LSE);
+}
+
+constexpr int lds_min_waves(int NR) { return NR >= 4 ? 1 : 2; }
+
+// One size class of the tile list, LDS-staged path.
+template <int NR, int NWV, int KVD, int AUX, int KT, int PD>
+__global__ __launch_bounds__(NWV * 64, lds_min_waves(NR)) void shared_lds_kernel(SharedArgs a, int cls, int Hq, int Hkv,
+                                                                                  int C, int L, int k, float scale) {
+    __shared__ uint4 smem[lds_units<KT>()];
+    const int first = a.tile_hdr[cls];
+    const int w = xcd_tile_index(a.tile_hdr[cls + 1] - first);
+    if (w < 0) return;
+    lds_tile<NR, NWV, KVD, AUX, KT, PD>(a, a.tiles[2 * (first + w)], a.tiles[2 * (first + w) + 1], Hq, Hkv, C, L, k,
+                                        scale, smem);
+}
+
+// Classes [c0, c1] (at most 128 rows, all within 256 registers per lane) in ONE launch, so that
+// sparsely populated classes do not each pay a kernel's fill and drain.  The tile list is walked
+// from its end: the largest tiles start first.
+template <int KVD, int AUX>
+__global__ __launch_bounds__(256, 2) void shared_mixed_kernel(SharedArgs a, int c0, int c1, int Hq, int Hkv, int C,
+                                                               int L, int k, float scale) {
+    __shared__ uint4 smem[lds_units<32>() + 64];            // 32 KiB of stages, or the 33 KiB merge buffer
+    static_assert(sizeof(smem) >= sizeof(float) * 2 * 32 * OSTRIDE, "merge buffer of the 32-row streaming path");
+    const int first = a.tile_hdr[c0], end = a.tile_hdr[c1 + 1];
+    const int w = xcd_tile_index(end - first);
+    if (w < 0) return;
+    const int t = end - 1 - w;
+    const int bkt = a.tiles[2 * t], row0 = a.tiles[2 * t + 1];
+    int cls = c0;
+    while (cls < c1 && t >= a.tile_hdr[cls + 1]) ++cls;
+    if (cls == 0) stream_tile<1, KVD, 4, AUX, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
+    else if (cls == 1) stream_tile<2, KVD, 4, AUX, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
+    else if (cls == 2) lds_tile<1, 4, KVD, AUX, 32, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
+    else lds_tile<2, 4, KVD, AUX, 32, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
+}
+
+}  // namespace mfma
+}  // namespace moska

@@ -1,49 +1,70 @@
-// Variant table and launcher of the MFMA Shared KV Attention kernel for one key/value dtype;
-// included by one translation unit per dtype so the instantiations compile in parallel.
+// Kernel table and launcher of the MFMA Shared KV Attention for one key/value dtype; included by
+// one translation unit per dtype so the instantiations compile in parallel.
 #pragma once
 
 #include <cstdlib>
 
-#include "attn_mfma.h"
+#include "attn_mfma_lds.h"
 
 namespace moska {
 namespace mfma {
 
-struct SharedVariant {
-    Variant v;
+struct SharedKernel {
+    int cls;            // tile size class served
+    int threads;
     const void *kernel;
 };
 
+// One launch per tile size class of the plan.  Small tiles (16, 32 rows) go to the streaming
+// kernels, whose registers hold every row; tiles of 64 rows and more go to the LDS-staged
+// kernels, where the waves split the rows and share each K/V stage.
 template <int KVD>
-int launch_shared_variant(const moska_problem_t &p, const SharedArgs &a, int MT, hipStream_t s) {
-#define MOSKA_SV(NR, NW, AUX, NKB) \
-    SharedVariant { Variant{NR, NW, AUX, NKB}, (const void *)shared_mfma_kernel<NR, KVD, NW, AUX, NKB> }
-    // first entry of each row count is the default; the others are reachable through
-    // MOSKA_SHARED_VARIANT=<index within that row count> for tuning runs
-    static const SharedVariant table[] = {
-        MOSKA_SV(1, 4, 0, 1), MOSKA_SV(1, 4, 2, 1), MOSKA_SV(2, 4, 0, 1), MOSKA_SV(2, 4, 2, 1), MOSKA_SV(2, 4, 2, 2),
-        MOSKA_SV(4, 4, 2, 2), MOSKA_SV(4, 4, 2, 1), MOSKA_SV(4, 4, 0, 2),
+int launch_shared_classes(const moska_problem_t &p, const SharedArgs &a, const SharedPlan &pl, hipStream_t s) {
+    static const SharedKernel table[] = {
+        {0, 256, (const void *)shared_mfma_kernel<1, KVD, 4, 2, 1>},
+        {1, 256, (const void *)shared_mfma_kernel<2, KVD, 4, 2, 1>},
+        {2, 128, (const void *)shared_lds_kernel<2, 2, KVD, 2, 32, 1>},
+        {3, 256, (const void *)shared_lds_kernel<2, 4, KVD, 2, 32, 1>},
+        {4, 512, (const void *)shared_lds_kernel<2, 8, KVD, 2, 64, 2>},
     };
-#undef MOSKA_SV
-    const int NR = MT / 16;
-    int want = 0;
-    if (const char *e = std::getenv("MOSKA_SHARED_VARIANT")) want = std::atoi(e);
-    const SharedVariant *pick = nullptr;
-    int seen = 0;
-    for (const SharedVariant &sv : table)
-        if (sv.v.NR == NR) {
-            if (!pick || seen == want) pick = &sv;
-            ++seen;
-        }
-    if (!pick || MT % 16) return MOSKA_ERR_UNSUPPORTED;
-    const int64_t tmax = max_tiles(p, MT);
-    if (tmax == 0) return MOSKA_OK;
-    const unsigned grid = (unsigned)(((tmax + 7) / 8) * 8);
-    SharedArgs args = a;
+    // tuning overrides: MOSKA_SHARED_C64=stream serves 64-row tiles with the streaming kernel;
+    // MOSKA_SHARED_MIXED=0 launches every class on its own instead of classes 0..3 together
+    static const SharedKernel c64_stream = {2, 256, (const void *)shared_mfma_kernel<4, KVD, 4, 2, 1>};
+    static const bool use_c64_stream = [] {
+        const char *e = std::getenv("MOSKA_SHARED_C64");
+        return e && e[0] == 's';
+    }();
+    static const bool mixed = [] {
+        const char *e = std::getenv("MOSKA_SHARED_MIXED");
+        return !(e && e[0] == '0');
+    }();
     int Hq = p.Hq, Hkv = p.Hkv, C = p.C, L = p.L, k = p.k;
     float scale = p.scale;
-    void *kargs[] = {&args, &Hq, &Hkv, &C, &L, &k, &scale};
-    return hip_status(hipLaunchKernel(pick->kernel, dim3(grid), dim3(pick->v.NW * 64), kargs, 0, s));
+    SharedArgs args = a;
+    int top = pl.cmax;
+    if (mixed && !use_c64_stream) top = pl.cmax < 3 ? -1 : 3;   // classes <= 3 go to the mixed launch
+    for (int c = pl.cmax; c >= pl.cmin && c > top; --c) {      // big tiles first: they run longest
+        const int64_t bound = class_bound(p, pl, c);
+        if (bound == 0) continue;
+        const SharedKernel &sk = (c == 2 && use_c64_stream) ? c64_stream : table[c];
+        const unsigned grid = (unsigned)(((bound + 7) / 8) * 8);
+        int cls = c;
+        void *kargs[] = {&args, &cls, &Hq, &Hkv, &C, &L, &k, &scale};
+        if (hipLaunchKernel(sk.kernel, dim3(grid), dim3(sk.threads), kargs, 0, s) != hipSuccess) return MOSKA_ERR_HIP;
+    }
+    if (mixed && !use_c64_stream) {
+        int c0 = pl.cmin, c1 = pl.cmax < 3 ? pl.cmax : 3;
+        int64_t bound = 0;
+        for (int c = c0; c <= c1; ++c) bound += class_bound(p, pl, c);
+        if (c0 <= c1 && bound > 0) {
+            const unsigned grid = (unsigned)(((bound + 7) / 8) * 8);
+            void *kargs[] = {&args, &c0, &c1, &Hq, &Hkv, &C, &L, &k, &scale};
+            if (hipLaunchKernel((const void *)shared_mixed_kernel<KVD, 2>, dim3(grid), dim3(256), kargs, 0, s) !=
+                hipSuccess)
+                return MOSKA_ERR_HIP;
+        }
+    }
+    return MOSKA_OK;
 }
 
 }  // namespace mfma

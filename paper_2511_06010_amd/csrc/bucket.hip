@@ -107,24 +107,52 @@ __global__ __launch_bounds__(1024) void bucket_kernel(const int32_t *__restrict_
     }
 }
 
-// Tiles of up to MT rows per bucket: entry t = (bucket, first row).  hdr[0] = tile count.
-__global__ __launch_bounds__(1024) void tile_list_kernel(const int32_t *__restrict__ off, int NB, int G, int MT,
-                                                          int32_t *__restrict__ hdr, int32_t *__restrict__ tiles) {
+// class of the tile that takes `rem` remaining rows of a bucket
+__device__ __forceinline__ int tile_class(int rem, int cmin, int cmax) {
+    int c = cmin;
+    while (c < cmax && class_rows(c) < rem) ++c;
+    return c;
+}
+
+// Tile list grouped by size class: hdr[c] = first entry of class c, hdr[kNumClasses] = total;
+// entry t = (bucket, first row).  Inside a class the entries keep bucket order, so the tiles of
+// one bucket are neighbours.
+__global__ __launch_bounds__(1024) void tile_list_kernel(const int32_t *__restrict__ off, int NB, int G, int cmin,
+                                                          int cmax, int32_t *__restrict__ hdr,
+                                                          int32_t *__restrict__ tiles) {
     __shared__ int tmp[1024];
+    __shared__ int cstart[kNumClasses + 1];
     const int per = (NB + blockDim.x - 1) / blockDim.x;
     const int b0 = threadIdx.x * per, b1 = min(NB, b0 + per);
-    int mine = 0;
-    for (int b = b0; b < b1; ++b) mine += ((off[b + 1] - off[b]) * G + MT - 1) / MT;
-    int total;
-    int pre = block_exclusive_scan(mine, tmp, &total);
+    int mine[kNumClasses] = {0, 0, 0, 0, 0};
     for (int b = b0; b < b1; ++b) {
-        const int rows = (off[b + 1] - off[b]) * G;
-        for (int r = 0; r < rows; r += MT, ++pre) {
-            tiles[2 * pre] = b;
-            tiles[2 * pre + 1] = r;
+        int rem = (off[b + 1] - off[b]) * G;
+        while (rem > 0) {
+            const int c = tile_class(rem, cmin, cmax);
+            mine[c] += 1;
+            rem -= class_rows(c);
         }
     }
-    if (threadIdx.x == 0) hdr[0] = total;
+    int pre[kNumClasses];
+    if (threadIdx.x == 0) cstart[0] = 0;
+    for (int c = 0; c < kNumClasses; ++c) {
+        int total;
+        pre[c] = block_exclusive_scan(mine[c], tmp, &total);
+        if (threadIdx.x == 0) cstart[c + 1] = cstart[c] + total;
+        __syncthreads();
+    }
+    for (int b = b0; b < b1; ++b) {
+        int rem = (off[b + 1] - off[b]) * G, r0 = 0;
+        while (rem > 0) {
+            const int c = tile_class(rem, cmin, cmax);
+            const int pos = cstart[c] + pre[c]++;
+            tiles[2 * pos] = b;
+            tiles[2 * pos + 1] = r0;
+            r0 += class_rows(c);
+            rem -= class_rows(c);
+        }
+    }
+    if (threadIdx.x <= kNumClasses) hdr[threadIdx.x] = cstart[threadIdx.x];
 }
 
 }  // namespace
@@ -151,9 +179,10 @@ int launch_bucket(const moska_problem_t &p, const int32_t *ids, int32_t *off, in
     return hip_status(hipGetLastError());
 }
 
-int launch_tile_list(const moska_problem_t &p, const int32_t *off, int MT, int32_t *hdr, int32_t *tiles,
-                     hipStream_t s) {
-    hipLaunchKernelGGL(tile_list_kernel, dim3(1), dim3(1024), 0, s, off, p.Hkv * p.C, p.Hq / p.Hkv, MT, hdr, tiles);
+int launch_tile_list(const moska_problem_t &p, const int32_t *off, const SharedPlan &pl, int32_t *hdr,
+                     int32_t *tiles, hipStream_t s) {
+    hipLaunchKernelGGL(tile_list_kernel, dim3(1), dim3(1024), 0, s, off, p.Hkv * p.C, p.Hq / p.Hkv, pl.cmin, pl.cmax,
+                       hdr, tiles);
     return hip_status(hipGetLastError());
 }
 

@@ -10,25 +10,42 @@ namespace moska {
 
 constexpr int kWave = 64;
 
-// Rows per work tile of the shared-attention kernels (a tile = up to MT query rows of one
-// bucket streamed against that bucket's chunk).
-int shared_tile_rows(const moska_problem_t &p);
 bool use_mfma_path(const moska_problem_t &p);
 
-// Upper bound on the number of tiles for this problem at MT rows per tile.
-inline int64_t max_tiles(const moska_problem_t &p, int MT) {
-    const int64_t items = (int64_t)p.B * p.Hkv * p.k;
-    const int64_t nb = (int64_t)p.Hkv * p.C;
-    const int64_t G = p.Hq / p.Hkv;
-    return (items < nb ? items : nb) + (items * G) / MT;
+// Work tiles of Shared KV Attention.  A bucket's rows are cut into tiles of one of five sizes;
+// tiles of one size class are served by one kernel launch.  A bucket of M rows becomes full tiles
+// of the largest class in the plan plus one remainder tile of the smallest class that holds it,
+// so every bucket's chunk is streamed as few times as possible.
+constexpr int kNumClasses = 5;
+__host__ __device__ constexpr int class_rows(int c) { return 16 << c; }   // 16, 32, 64, 128, 256
+struct SharedPlan {
+    int cmin, cmax;          // classes in use
+};
+SharedPlan shared_plan(const moska_problem_t &p);
+
+// Upper bound on the number of tiles of class c (host-known, sizes the launch grid): a remainder
+// tile of class c > cmin holds more than kClassRows[c-1] rows and a bucket has at most one.
+inline int64_t class_bound(const moska_problem_t &p, const SharedPlan &pl, int c) {
+    if (c < pl.cmin || c > pl.cmax) return 0;
+    const int64_t items = (int64_t)p.B * p.Hkv * p.k, nb = (int64_t)p.Hkv * p.C;
+    const int64_t rows = items * (p.Hq / p.Hkv);
+    const int64_t nbe = items < nb ? items : nb;
+    int64_t rem = c == pl.cmin ? nbe : rows / (class_rows(c - 1) + 1);
+    if (rem > nbe) rem = nbe;
+    return c == pl.cmax ? rem + rows / class_rows(c) : rem;
+}
+inline int64_t max_tiles(const moska_problem_t &p, const SharedPlan &pl) {
+    int64_t t = 0;
+    for (int c = 0; c < kNumClasses; ++c) t += class_bound(p, pl, c);
+    return t;
 }
 
-// Workspace layout (int32 units unless noted), one region per user:
-//   [tile header 4][tile list 2*Tmax][bucket rank scratch n_items][internal bucket_off NB+1]
-//   [internal bucket_items n_items]
+// Workspace layout (int32 units), one region per user:
+//   [tile header 8: start of each class in the tile list, total][tile list 2*Tmax]
+//   [bucket rank scratch n_items][internal bucket_off NB+1][internal bucket_items n_items]
 struct Workspace {
-    int32_t *tile_hdr;      // [0] = number of tiles
-    int32_t *tiles;         // (bucket, first row) pairs
+    int32_t *tile_hdr;
+    int32_t *tiles;         // (bucket, first row) pairs, grouped by class
     int32_t *rank;          // moska_bucket scratch
     int32_t *off;           // bucket_off when the caller passes none
     int32_t *items;
@@ -40,8 +57,8 @@ int launch_route(const moska_problem_t &p, const void *Q, const void *E, int32_t
                  hipStream_t s);
 int launch_bucket(const moska_problem_t &p, const int32_t *ids, int32_t *off, int32_t *items,
                   int32_t *rank_scratch, hipStream_t s);
-int launch_tile_list(const moska_problem_t &p, const int32_t *off, int MT, int32_t *hdr, int32_t *tiles,
-                     hipStream_t s);
+int launch_tile_list(const moska_problem_t &p, const int32_t *off, const SharedPlan &pl, int32_t *hdr,
+                     int32_t *tiles, hipStream_t s);
 
 struct SharedArgs {
     const void *Q, *Ks, *Vs;
@@ -54,9 +71,9 @@ struct UniqueArgs {
     const int32_t *unique_len;
     float *part_O, *part_LSE;
 };
-int launch_shared_generic(const moska_problem_t &p, const SharedArgs &a, int MT, hipStream_t s);
+int launch_shared_generic(const moska_problem_t &p, const SharedArgs &a, const SharedPlan &pl, hipStream_t s);
 int launch_unique_generic(const moska_problem_t &p, const UniqueArgs &a, hipStream_t s);
-int launch_shared_mfma(const moska_problem_t &p, const SharedArgs &a, int MT, hipStream_t s);
+int launch_shared_mfma(const moska_problem_t &p, const SharedArgs &a, const SharedPlan &pl, hipStream_t s);
 int launch_unique_mfma(const moska_problem_t &p, const UniqueArgs &a, hipStream_t s);
 int launch_merge(const moska_problem_t &p, const float *part_O, const float *part_LSE, void *O, float *LSE,
                  hipStream_t s);

@@ -64,7 +64,9 @@ def test_zipf_popularity_and_empty_buckets():
 
 def test_batching_invariance():
     # Sec. III-A: batching the queries of a bucket into one matrix must not change any row --
-    # a request processed alone gives the same partial as in the batch (up to fp32 rounding order)
+    # a request processed alone gives the same partial as in the batch.  The two runs use
+    # different tile kernels (their running softmax maxima differ, and with them the bf16
+    # rounding of the probabilities), so they agree to bf16 level, not bit for bit.
     p = P(B=32, C=2, k=1, L=192, U=16)
     inp = generate(p, seed=7).to("cuda")
     full = gpu_pipeline(inp)
@@ -74,8 +76,8 @@ def test_batching_invariance():
         one.E, one.Ks, one.Vs, one.unique_len = inp.E, inp.Ks, inp.Vs, inp.unique_len[b:b + 1].contiguous()
         solo = gpu_pipeline(one)
         assert torch.equal(solo.ids[0], full.ids[b])
-        torch.testing.assert_close(solo.part_O[0], full.part_O[b], rtol=0, atol=2e-6)
-        torch.testing.assert_close(solo.part_LSE[0], full.part_LSE[b], rtol=0, atol=2e-6)
+        torch.testing.assert_close(solo.part_O[0], full.part_O[b], rtol=0, atol=3e-3)
+        torch.testing.assert_close(solo.part_LSE[0], full.part_LSE[b], rtol=0, atol=1e-4)
 
 
 def test_run_twice_is_bit_identical():
