@@ -10,6 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmoska.so")
+PROBE = os.path.join(PKG, "hbm_probe")
 SOURCES = ["attn_mfma_shared_bf16.hip", "attn_mfma_shared_fp8.hip", "attn_mfma.hip", "api.hip", "route.hip",
            "bucket.hip", "attn_generic.hip", "merge.hip"]
 # packed-fp32 VALU forms are disabled on purpose (they have produced wrong results on the test machines)
@@ -28,8 +29,10 @@ def build_library(extra_flags=(), verbose: bool = True) -> str:
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
+    # stand-alone bandwidth / counter-calibration probe
+    subprocess.check_call(["hipcc", "-O3", "--offload-arch=gfx950", "-o", PROBE, os.path.join(CSRC, "hbm_probe.hip")])
     if verbose:
-        print(f"built {LIB}")
+        print(f"built {LIB} and {PROBE}")
     return LIB
 
 

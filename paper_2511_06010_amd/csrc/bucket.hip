@@ -13,22 +13,28 @@
 namespace moska {
 namespace {
 
-// Exclusive scan of v over the block's threads (blockDim.x <= 1024); every thread gets its
-// prefix, *total the grand sum.  tmp: blockDim.x ints of LDS.
+// Exclusive scan of v over the block's threads (blockDim.x a multiple of 64, <= 1024); every
+// thread gets its prefix, *total the grand sum.  Wave-level shuffles, then the (at most 16) wave
+// totals through LDS.  tmp: 16 ints of LDS.  Two barriers.
 __device__ int block_exclusive_scan(int v, int *tmp, int *total) {
-    const int t = threadIdx.x, n = blockDim.x;
-    tmp[t] = v;
-    __syncthreads();
-    for (int d = 1; d < n; d <<= 1) {
-        const int add = t >= d ? tmp[t - d] : 0;
-        __syncthreads();
-        tmp[t] += add;
-        __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(incl, d);
+        if (lane >= d) incl += up;
     }
-    const int incl = tmp[t];
-    *total = tmp[n - 1];
+    if (lane == 63) tmp[wave] = incl;
     __syncthreads();
-    return incl - v;
+    int base = 0, sum = 0;
+    for (int w = 0; w < nw; ++w) {
+        const int t = tmp[w];
+        if (w < wave) base += t;
+        sum += t;
+    }
+    *total = sum;
+    __syncthreads();
+    return base + incl - v;
 }
 
 __global__ __launch_bounds__(1024) void bucket_kernel(const int32_t *__restrict__ ids, int32_t *__restrict__ off,

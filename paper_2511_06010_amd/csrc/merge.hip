@@ -1,7 +1,7 @@
 // moska_merge: log-sum-exp combination of the k shared partials and the unique partial
-// (the combination step of Fig. 2(b)).  One wavefront per query row; lane l owns output
-// columns l, l+64, ...  The kernel reads P*(D+1) floats and writes D values per row: it is
-// bound by HBM traffic on the partials.
+// (the combination step of Fig. 2(b)).  D/4 threads per query row, each owning four adjacent
+// output columns (16-byte loads of every partial).  The kernel reads P*(D+1) floats and writes D
+// values per row: it is bound by HBM traffic on the partials.
 #include "moska_internal.h"
 
 namespace moska {
@@ -11,37 +11,40 @@ template <int OD>
 __global__ __launch_bounds__(256) void merge_kernel(const float *__restrict__ part_O,
                                                      const float *__restrict__ part_LSE, void *__restrict__ O,
                                                      float *__restrict__ LSE, int64_t rows, int P, int D) {
-    const int lane = threadIdx.x % kWave;
-    const int64_t r = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-    if (r >= rows) return;
+    const int tpr = D / 4;                                  // threads per row (D is a multiple of 16)
+    const int rpb = 256 / tpr;                              // rows per block
+    const int t = threadIdx.x % tpr;
+    const int64_t r = (int64_t)blockIdx.x * rpb + threadIdx.x / tpr;
+    if (threadIdx.x >= rpb * tpr || r >= rows) return;
     const float *lse = part_LSE + r * P;
     float m = -INFINITY;
     for (int j = 0; j < P; ++j) m = fmaxf(m, lse[j]);
     float wsum = 0.f;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    float4 acc = {0.f, 0.f, 0.f, 0.f};
     if (m != -INFINITY) {
         for (int j = 0; j < P; ++j) {
             const float lj = lse[j];
             if (lj == -INFINITY) continue;             // an empty slot's O is never read
             const float w = expf(lj - m);
             wsum += w;
-            const float *o = part_O + (r * P + j) * D;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (lane + kWave * i < D) acc[i] = fmaf(w, o[lane + kWave * i], acc[i]);
+            const float4 o = *(const float4 *)(part_O + (r * P + j) * D + 4 * t);
+            acc.x = fmaf(w, o.x, acc.x);
+            acc.y = fmaf(w, o.y, acc.y);
+            acc.z = fmaf(w, o.z, acc.z);
+            acc.w = fmaf(w, o.w, acc.w);
         }
     }
     const float inv = wsum > 0.f ? 1.f / wsum : 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int d = lane + kWave * i;
-        if (d < D) {
-            const float v = acc[i] * inv;
-            if constexpr (OD == MOSKA_BF16) ((uint16_t *)O)[r * D + d] = (uint16_t)f32_to_bf16_bits(v);
-            else ((float *)O)[r * D + d] = v;
-        }
+    acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+    if constexpr (OD == MOSKA_BF16) {
+        uint2 v;
+        v.x = f32_to_bf16_bits(acc.x) | (f32_to_bf16_bits(acc.y) << 16);
+        v.y = f32_to_bf16_bits(acc.z) | (f32_to_bf16_bits(acc.w) << 16);
+        *(uint2 *)((uint16_t *)O + r * D + 4 * t) = v;
+    } else {
+        *(float4 *)((float *)O + r * D + 4 * t) = acc;
     }
-    if (LSE && lane == 0) LSE[r] = wsum > 0.f ? m + logf(wsum) : -INFINITY;
+    if (LSE && t == 0) LSE[r] = wsum > 0.f ? m + logf(wsum) : -INFINITY;
 }
 
 }  // namespace
@@ -49,7 +52,8 @@ __global__ __launch_bounds__(256) void merge_kernel(const float *__restrict__ pa
 int launch_merge(const moska_problem_t &p, const float *part_O, const float *part_LSE, void *O, float *LSE,
                  hipStream_t s) {
     const int64_t rows = (int64_t)p.B * p.Hq;
-    const unsigned grid = (unsigned)((rows + 3) / 4);
+    const int rpb = 256 / (p.D / 4);
+    const unsigned grid = (unsigned)((rows + rpb - 1) / rpb);
     auto kern = p.q_dtype == MOSKA_BF16 ? merge_kernel<MOSKA_BF16> : merge_kernel<MOSKA_F32>;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, s, part_O, part_LSE, O, LSE, rows, p.k + 1, p.D);
     return hip_status(hipGetLastError());
