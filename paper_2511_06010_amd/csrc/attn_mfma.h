@@ -40,6 +40,7 @@ constexpr int HD = 128;                       // head size served here
 constexpr int OSTRIDE = HD + 4;               // LDS row: 128 outputs, max, sum, pad
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kLazy = 8.f;                  // log2 units, see softmax_tile
 constexpr uint32_t kSelLo = 0x05040100u;      // v_perm: (lo16 of b) | (lo16 of a) << 16
 constexpr uint32_t kSelHi = 0x07060302u;      // v_perm: (hi16 of b) | (hi16 of a) << 16
 
@@ -52,6 +53,21 @@ __device__ __forceinline__ f32x4 mfma16(const uint32_t (&a)[4], const uint32_t (
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // round to nearest even
     const f32x2 v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// Reductions over the four lanes x, x+16, x+32, x+48 that share a query row, on the vector ALU
+// (v_permlane16_swap / v_permlane32_swap hand every lane both members of its xor-16 / xor-32 pair).
+__device__ __forceinline__ float row_lanes_max(float v) {
+    auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float row_lanes_sum(float v) {
+    auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
 template <int KVD> constexpr int row_bytes() { return KVD == MOSKA_BF16 ? 2 * HD : HD; }
@@ -169,7 +185,8 @@ __device__ __forceinline__ void qk_tile(f32x4 (&s)[NR][2], const uint32_t (&qf)[
     }
 }
 
-// online softmax in the log2 domain; produces the P^T operands and rescales O when a max moved
+// online softmax in the log2 domain; produces the P^T operands and rescales O when a max moved.
+// sc > 0 folds the logit scale, the dequantisation factor of the keys and log2(e).
 template <int NR, bool TAIL>
 __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)[NR][2], uint32_t (&pf)[NR][4],
                                              int key0, int nkeys, float sc, int q) {
@@ -180,20 +197,22 @@ __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)
         for (int kblk = 0; kblk < 2; ++kblk)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                float z = s[rb][kblk][r] * sc;
+                float z = s[rb][kblk][r];
                 if (TAIL && key0 + 16 * kblk + 4 * q + r >= nkeys) z = -INFINITY;   // rows past the end read as 0
                 v[4 * kblk + r] = z;
             }
         float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float mn = fmaxf(st.m[rb], mx);        // finite: every tile holds at least one real key
-        const float alpha = __builtin_amdgcn_exp2f(st.m[rb] - mn);
+        mx = row_lanes_max(mx) * sc;
+        // The reference point of a row moves only when the tile's maximum exceeds it by more than
+        // kLazy (a factor 2^kLazy in the probabilities, harmless in fp32 sums and in bf16's
+        // exponent range); otherwise alpha is exactly 1 and the accumulators are left alone.
+        const float mn = mx > st.m[rb] + kLazy ? mx : st.m[rb];   // first tile: m = -inf, always moves; finite after
+        const float alpha = __builtin_amdgcn_exp2f(st.m[rb] - mn);  // exactly 1 unless the reference moved
         st.m[rb] = mn;
         float sum = 0.f;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            v[i] = __builtin_amdgcn_exp2f(v[i] - mn);
+            v[i] = __builtin_amdgcn_exp2f(fmaf(v[i], sc, -mn));
             sum += v[i];
         }
         st.l[rb] = st.l[rb] * alpha + sum;
@@ -294,7 +313,9 @@ __device__ __forceinline__ void attend(WaveState<NR> &st, const uint32_t (&qf)[N
 
 // Normalise and write the rows a wave holds (st.l already summed over the row's four lanes).
 // orow[rb]: index of row 16rb+x in part_LSE (part_O row = orow*HD), or -1 for a padding row.
-template <int NR>
+// DIMS16 = false: component r of o[rb][e] is dim 32q + 8r + e (operands transposed in registers);
+// DIMS16 = true:  it is dim 16e + 4q + r (operands from the LDS transpose read).
+template <int NR, bool DIMS16 = false>
 __device__ __forceinline__ void store_rows(const WaveState<NR> &st, int q, const int64_t (&orow)[NR], float vmul,
                                            float *part_O, float *part_LSE) {
 #pragma unroll
@@ -302,13 +323,22 @@ __device__ __forceinline__ void store_rows(const WaveState<NR> &st, int q, const
         if (orow[rb] < 0) continue;
         const float l = st.l[rb];
         const float inv = l > 0.f ? vmul / l : 0.f;
-        float *o = part_O + orow[rb] * HD + 32 * q;
+        if constexpr (DIMS16) {
+            float *o = part_O + orow[rb] * HD + 4 * q;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float4 lo = {st.o[rb][0][r] * inv, st.o[rb][1][r] * inv, st.o[rb][2][r] * inv, st.o[rb][3][r] * inv};
-            const float4 hi = {st.o[rb][4][r] * inv, st.o[rb][5][r] * inv, st.o[rb][6][r] * inv, st.o[rb][7][r] * inv};
-            *(float4 *)(o + 8 * r) = lo;
-            *(float4 *)(o + 8 * r + 4) = hi;
+            for (int e = 0; e < 8; ++e) {
+                const float4 v = {st.o[rb][e][0] * inv, st.o[rb][e][1] * inv, st.o[rb][e][2] * inv, st.o[rb][e][3] * inv};
+                *(float4 *)(o + 16 * e) = v;
+            }
+        } else {
+            float *o = part_O + orow[rb] * HD + 32 * q;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float4 lo = {st.o[rb][0][r] * inv, st.o[rb][1][r] * inv, st.o[rb][2][r] * inv, st.o[rb][3][r] * inv};
+                const float4 hi = {st.o[rb][4][r] * inv, st.o[rb][5][r] * inv, st.o[rb][6][r] * inv, st.o[rb][7][r] * inv};
+                *(float4 *)(o + 8 * r) = lo;
+                *(float4 *)(o + 8 * r + 4) = hi;
+            }
         }
         if (q == 0) part_LSE[orow[rb]] = l > 0.f ? (st.m[rb] + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
     }
@@ -322,10 +352,7 @@ __device__ __forceinline__ void combine_and_store(WaveState<NR> &st, float *lds,
     constexpr int R = 16 * NR;
 #pragma unroll
     for (int rb = 0; rb < NR; ++rb) {
-        float l = st.l[rb];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
-        st.l[rb] = l;
+        st.l[rb] = row_lanes_sum(st.l[rb]);
     }
 #pragma unroll
     for (int s = NW / 2; s >= 1; s >>= 1) {

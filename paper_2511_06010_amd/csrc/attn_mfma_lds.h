@@ -8,11 +8,11 @@
 // LDS buffer (an fp8 store is widened to bf16 here, once per workgroup instead of once per
 // wave).  One barrier per stage.
 //
-// LDS stage layout (bf16): K[32 keys][256 B] with the 16-byte units of a row XOR-swizzled by
+// LDS stage layout (bf16): K[keys][256 B] with the 16-byte units of a row XOR-swizzled by
 // (key & 15), so the MFMA A-operand read (16 keys x one unit, 16 lanes per phase) is free of bank
-// conflicts; V[32 keys][256 B] plain (its reads take whole rows).  The waves read operands in
-// the same lane layout as the streaming kernels (attn_mfma.h) and reuse their MFMA / softmax
-// code.
+// conflicts; V[keys][256 B] with the 32-byte dim blocks of a row XOR-swizzled by (key & 7) for the
+// transpose read that builds the V^T operand without any register shuffling.  Scores and softmax
+// reuse the code of the streaming kernels (attn_mfma.h).
 #pragma once
 
 #include "attn_mfma.h"
@@ -58,7 +58,7 @@ __device__ __forceinline__ void stage_store(const StageRegs<KVD, T, KT> &r, uint
         if constexpr (KVD == MOSKA_BF16) {
             const int row = g >> 4, u = g & 15;
             lk[row * 16 + (u ^ (row & 15))] = r.k[i];
-            lv[g] = r.v[i];
+            lv[row * 16 + ((((u >> 1) ^ (row & 7)) << 1) | (u & 1))] = r.v[i];
         } else {
             const int row = g >> 3, u = (g & 7) * 2;       // 8 fp8 units per key row -> bf16 units u, u+1
             uint4 lo, hi;
@@ -66,22 +66,59 @@ __device__ __forceinline__ void stage_store(const StageRegs<KVD, T, KT> &r, uint
             lk[row * 16 + (u ^ (row & 15))] = lo;
             lk[row * 16 + ((u + 1) ^ (row & 15))] = hi;
             fp8x16_to_bf16(r.v[i], lo, hi);
-            lv[row * 16 + u] = lo;
-            lv[row * 16 + u + 1] = hi;
+            const int vb = ((g & 7) ^ (row & 7)) * 2;   // 32-byte block swizzle of the value rows
+            lv[row * 16 + vb] = lo;
+            lv[row * 16 + vb + 1] = hi;
         }
     }
 }
 
-// MFMA operands of one 32-key sub-tile out of LDS, in the register layout of the streaming kernels
-__device__ __forceinline__ void stage_read_k(TileK<MOSKA_BF16> &t, const uint4 *lk, int q, int x) {
+// S^T of one 32-key sub-tile with the key operands read from LDS one 16-key block at a time
+// (lane layout as in the streaming kernels; the XOR swizzle makes the reads conflict free)
+template <int NR>
+__device__ __forceinline__ void qk_from_lds(f32x4 (&s)[NR][2], const uint32_t (&qf)[NR][4][4], const uint4 *lk, int q,
+                                            int x) {
 #pragma unroll
-    for (int kblk = 0; kblk < 2; ++kblk)
+    for (int kblk = 0; kblk < 2; ++kblk) {
+        uint32_t kf[4][4];
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) t.k[kblk][kb] = lk[(16 * kblk + x) * 16 + ((4 * kb + q) ^ x)];
+        for (int kb = 0; kb < 4; ++kb) {
+            const uint4 v = lk[(16 * kblk + x) * 16 + ((4 * kb + q) ^ x)];
+            kf[kb][0] = v.x; kf[kb][1] = v.y; kf[kb][2] = v.z; kf[kb][3] = v.w;
+        }
+#pragma unroll
+        for (int rb = 0; rb < NR; ++rb) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) acc = mfma16(kf[kb], qf[rb][kb], acc);
+            s[rb][kblk] = acc;
+        }
+    }
 }
-__device__ __forceinline__ void stage_read_v(TileV<MOSKA_BF16> &t, const uint4 *lv, int q, int x) {
+
+// O^T += V^T P^T of one 32-key sub-tile with the V^T operand fetched by the LDS transpose read
+// (ds_read_b64_tr_b16): inside a 16-lane group, source lane S reads four consecutive dims of key
+// row S/4 and result lane x receives dim x of the four rows -- exactly the MFMA A operand
+// (dim x of 4 key slots).  MFMA e covers dims 16e..16e+15, so component r of o[rb][e] is dim
+// 16e + 4q + r.  The 32-byte dim blocks of a value row are XOR-swizzled by (key & 7): the 16 keys
+// of a read land on 8 different blocks (2-way bank conflict at worst).
+template <int NR>
+__device__ __forceinline__ void pv_from_lds(WaveState<NR> &st, const uint4 *lv, const uint32_t (&pf)[NR][4], int lane) {
+    typedef __attribute__((ext_vector_type(4))) short s16x4;
+    typedef __attribute__((address_space(3))) s16x4 *lds_s16x4;
+    const int q = lane >> 4, S = lane & 15;
+    const int key = 4 * q + (S >> 2);                       // and key + 16 for slots 4..7
+    const char *rowp = (const char *)lv + key * 256 + (S & 3) * 8;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) t.v[s] = lv[(4 * q + slot_row(s)) * 16 + x];
+    for (int e = 0; e < 8; ++e) {
+        const char *p = rowp + ((e ^ (key & 7)) << 5);
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)p);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(p + 16 * 256));
+        const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
+        const uint32_t vf[4] = {l2.x, l2.y, h2.x, h2.y};
+#pragma unroll
+        for (int rb = 0; rb < NR; ++rb) st.o[rb][e] = mfma16(vf, pf[rb], st.o[rb][e]);
+    }
 }
 
 // LDS footprint of a tile kernel, in uint4 units: two buffers of K and V stages
@@ -143,17 +180,13 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
     auto consume = [&](int t, int cur) {
 #pragma unroll
         for (int sub = 0; sub < KT / 32; ++sub) {
-            TileK<MOSKA_BF16> tk;
-            TileV<MOSKA_BF16> tv;
             f32x4 s[NR][2];
             uint32_t pf[NR][4];
             const int key0 = KT * t + 32 * sub;
-            stage_read_k(tk, ldsK + cur * SU + sub * 512, q, x);
-            qk_tile<NR, MOSKA_BF16>(s, qf, tk);
+            qk_from_lds<NR>(s, qf, ldsK + cur * SU + sub * 512, q, x);
             if (key0 + 32 > L) softmax_tile<NR, true>(st, s, pf, key0, L, sc, q);
             else softmax_tile<NR, false>(st, s, pf, key0, L, sc, q);
-            stage_read_v(tv, ldsV + cur * SU + sub * 512, q, x);
-            pv_tile<NR, MOSKA_BF16>(st, tv, pf);
+            pv_from_lds<NR>(st, ldsV + cur * SU + sub * 512, pf, lane);
         }
     };
     stage_fetch<KVD, T, KT, AUX>(regs[0], rk, rv, 0, tid);
@@ -187,12 +220,9 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
     }
 #pragma unroll
     for (int rb = 0; rb < NR; ++rb) {
-        float l = st.l[rb];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
-        st.l[rb] = l;
+        st.l[rb] = row_lanes_sum(st.l[rb]);
     }
-    store_rows<NR>(st, q, orow, vmul, a.part_O, a.part_LSE);
+    store_rows<NR, true>(st, q, orow, vmul, a.part_O, a.part_LSE);
 }
 
 constexpr int lds_min_waves(int NR) { return NR >= 4 ? 1 : 2; }
@@ -212,10 +242,12 @@ __global__ __launch_bounds__(NWV * 64, lds_min_waves(NR)) void shared_lds_kernel
 // Classes [c0, c1] (at most 128 rows, all within 256 registers per lane) in ONE launch, so that
 // sparsely populated classes do not each pay a kernel's fill and drain.  The tile list is walked
 // from its end: the largest tiles start first.
+constexpr int MIXED_KT = 64;       // keys per LDS stage of the mixed launch (64 KiB of stages per workgroup)
+
 template <int KVD, int AUX>
 __global__ __launch_bounds__(256, 2) void shared_mixed_kernel(SharedArgs a, int c0, int c1, int Hq, int Hkv, int C,
                                                                int L, int k, float scale) {
-    __shared__ uint4 smem[lds_units<32>() + 64];            // 32 KiB of stages, or the 33 KiB merge buffer
+    __shared__ uint4 smem[lds_units<MIXED_KT>()];           // K/V stages, or the 33 KiB merge buffer
     static_assert(sizeof(smem) >= sizeof(float) * 2 * 32 * OSTRIDE, "merge buffer of the 32-row streaming path");
     const int first = a.tile_hdr[c0], end = a.tile_hdr[c1 + 1];
     const int w = xcd_tile_index(end - first);
@@ -226,8 +258,10 @@ __global__ __launch_bounds__(256, 2) void shared_mixed_kernel(SharedArgs a, int 
     while (cls < c1 && t >= a.tile_hdr[cls + 1]) ++cls;
     if (cls == 0) stream_tile<1, KVD, 4, AUX, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
     else if (cls == 1) stream_tile<2, KVD, 4, AUX, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
-    else if (cls == 2) lds_tile<1, 4, KVD, AUX, 32, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
-    else lds_tile<2, 4, KVD, AUX, 32, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
+    else {
+        if (cls == 2) lds_tile<1, 4, KVD, AUX, MIXED_KT, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
+        else lds_tile<2, 4, KVD, AUX, MIXED_KT, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
+    }
 }
 
 }  // namespace mfma

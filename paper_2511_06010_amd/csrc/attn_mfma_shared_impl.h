@@ -59,8 +59,7 @@ int launch_shared_classes(const moska_problem_t &p, const SharedArgs &a, const S
         if (c0 <= c1 && bound > 0) {
             const unsigned grid = (unsigned)(((bound + 7) / 8) * 8);
             void *kargs[] = {&args, &c0, &c1, &Hq, &Hkv, &C, &L, &k, &scale};
-            if (hipLaunchKernel((const void *)shared_mixed_kernel<KVD, 2>, dim3(grid), dim3(256), kargs, 0, s) !=
-                hipSuccess)
+            if (hipLaunchKernel((const void *)shared_mixed_kernel<KVD, 2>, dim3(grid), dim3(256), kargs, 0, s) != hipSuccess)
                 return MOSKA_ERR_HIP;
         }
     }
