@@ -53,6 +53,19 @@ def test_small_problem_matches_oracle(name):
     check_against_oracle(generate(p, seed=101, unique_len=ragged), name)
 
 
+def test_config0_matches_stored_oracle_values():
+    # expected values stored by tests/golden/make_config0_golden.py (oracle only)
+    from test_oracle_pins import read_config0_golden
+    ids, O, LSE = read_config0_golden()
+    buf = gpu_pipeline(generate(config(0), seed=20251106).to("cuda"))
+    for b in range(8):
+        assert buf.ids[b, 0].tolist() == [int(c) for c in ids[b]]
+        want = torch.tensor(O[b], dtype=torch.float64)
+        got = buf.O[b, 0, :8].double().cpu()
+        assert (got - want).abs().max() <= 1e-5 * want.abs().max()
+        torch.testing.assert_close(buf.LSE[b].double().cpu(), torch.tensor(LSE[b], dtype=torch.float64), rtol=1e-5, atol=1e-5)
+
+
 def test_zipf_popularity_and_empty_buckets():
     # strongly skewed targets: one very hot bucket, many buckets that receive nothing
     p = P(B=64, Hq=8, Hkv=2, C=40, L=96, k=2, U=50, popularity="zipf", zipf_s=2.0)

@@ -307,3 +307,24 @@ def test_config0_shapes_and_self_consistency():
     np.testing.assert_allclose(st.O.numpy(), st.O_direct.numpy(), rtol=1e-12, atol=1e-14)
     O, LSE = dense_reference(inp, st.ids)
     np.testing.assert_allclose(st.O.numpy(), O, rtol=1e-12, atol=1e-14)
+
+
+def read_config0_golden():
+    ids, O, LSE = {}, {}, {}
+    for line in open(os.path.join(GOLDEN, "config0_oracle.txt")):
+        f = line.split("#")[0].split()
+        if not f:
+            continue
+        tgt = {"ids": ids, "O": O, "LSE": LSE}[f[0]]
+        tgt[int(f[1])] = [float(x) for x in f[2:]]
+    return ids, O, LSE
+
+
+def test_config0_matches_stored_oracle_values():
+    # regression pin: the oracle (and the generator) still produce the stored configuration-0 values
+    ids, O, LSE = read_config0_golden()
+    st = oracle.decode_step(generate(config(0), seed=20251106))
+    for b in range(8):
+        assert [int(c) for c in st.ids[b, 0]] == [int(c) for c in ids[b]]
+        np.testing.assert_allclose(st.O_direct[b, 0, :8].numpy(), O[b], rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(st.LSE_direct[b].numpy(), LSE[b], rtol=1e-13)
