@@ -127,6 +127,20 @@ int moska_decode_step(const moska_problem_t *p, const void *Q, const void *E,
                       float *part_O, float *part_LSE, void *O, float *LSE,
                       void *ws, size_t ws_bytes, void *stream);
 
+/* Offline construction of the shared store (Sec. III-A: pre-computed shared KV caches;
+ * Sec. III-B: precomputed chunk embeddings).  Not part of the decode step.
+ *
+ * moska_chunk_embeddings: E[h,c,:] = mean over the L stored keys of chunk c on KV head h
+ * (times scale_k[c,h] for an FP8 store), accumulated in fp64, rounded to q_dtype.
+ *   Ks [C,Hkv,L,D] shared_kv_dtype, scale_k [C,Hkv] f32 (FP8 only, else NULL), E [Hkv,C,D] q_dtype out.
+ *
+ * moska_quantize_shared: per (chunk, KV head) block scale = max|x| / 448 (at least 1e-30) and
+ * X8 = round-to-nearest-even e4m3fn of x / scale, saturating; both divisions in f32.
+ *   X [C,Hkv,L,D] bf16 (q_dtype must be BF16, shared_kv_dtype FP8), X8 same shape fp8 out,
+ *   scale [C,Hkv] f32 out.  Call once for K and once for V. */
+int moska_chunk_embeddings(const moska_problem_t *p, const void *Ks, const float *scale_k, void *E, void *stream);
+int moska_quantize_shared(const moska_problem_t *p, const void *X, void *X8, float *scale, void *stream);
+
 /* Static description of a status code. */
 const char *moska_status_string(int status);
 

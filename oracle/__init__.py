@@ -42,7 +42,7 @@ def lib():
     if _lib is None:
         _lib = ctypes.CDLL(build())
         for name in ("mo_widen", "mo_route", "mo_bucket", "mo_attend", "mo_partials", "mo_direct", "mo_merge",
-                     "mo_threads"):
+                     "mo_threads", "mo_chunk_embeddings", "mo_quantize_fp8"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -197,3 +197,24 @@ def decode_step(inp, ids: Optional[torch.Tensor] = None, want_direct: bool = Tru
     O, LSE = merge(pO, pL)
     Od, Ld = direct(inp, ids) if want_direct else (None, None)
     return DecodeStep(ids, scores, off, items, pO, pL, O, LSE, Od, Ld)
+
+
+def chunk_embeddings(p, Ks, scale_k=None):
+    """Mean key of every (chunk, KV head) block, rounded to the q dtype.  Returns E [Hkv,C,D]."""
+    _check(Ks, (p.C, p.Hkv, p.L, p.D), p.kv_dtype)
+    E = torch.empty((p.Hkv, p.C, p.D), dtype={"f32": torch.float32, "bf16": torch.bfloat16}[p.q_dtype])
+    cp = _cprob(p)
+    rc = lib().mo_chunk_embeddings(ctypes.byref(cp), _ptr(Ks), _ptr(scale_k), _ptr(E))
+    assert rc == 0
+    return E
+
+
+def quantize_fp8(p, X):
+    """X [C,Hkv,L,D] (q dtype) -> (fp8 tensor, scale [C,Hkv] f32) with X ~= scale * fp8."""
+    _check(X, (p.C, p.Hkv, p.L, p.D), p.q_dtype)
+    X8 = torch.empty((p.C, p.Hkv, p.L, p.D), dtype=torch.uint8)
+    scale = torch.empty((p.C, p.Hkv), dtype=torch.float32)
+    cp = _cprob(p)
+    rc = lib().mo_quantize_fp8(ctypes.byref(cp), _ptr(X), _ptr(X8), _ptr(scale))
+    assert rc == 0
+    return X8.view(torch.float8_e4m3fn), scale

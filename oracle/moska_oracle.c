@@ -311,3 +311,76 @@ int mo_merge(int64_t rows, int P, int D, const double *part_O, const double *par
     }
     return 0;
 }
+
+/* ---- offline construction of the shared store (Sec. III-A/B: pre-computed caches and
+ *      precomputed chunk embeddings) --------------------------------------------------------- */
+
+/* round-to-nearest-even f64 -> bf16 bits via f32 (the value is first rounded to f32, as a GPU
+ * kernel that accumulates in f64 and stores through f32 does) */
+static uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+/* E[h,c,:] = mean over the L tokens of the stored keys of chunk c on KV head h (dequantised
+ * when the store is fp8), accumulated in fp64, rounded to the q dtype (f32 or bf16). */
+int mo_chunk_embeddings(const mo_problem *p, const void *Ks, const float *scale_k, void *E) {
+    if (p->q_dtype != MO_F32 && p->q_dtype != MO_BF16) return -1;
+    for (int c = 0; c < p->C; ++c)
+        for (int h = 0; h < p->Hkv; ++h) {
+            const double mul = scale_k ? (double)scale_k[c * p->Hkv + h] : 1.0;
+            const int64_t base = ((int64_t)c * p->Hkv + h) * p->L * p->D;
+            for (int d = 0; d < p->D; ++d) {
+                double a = 0.0;
+                for (int t = 0; t < p->L; ++t) a += load_as_f64(p->kv_dtype, Ks, base + (int64_t)t * p->D + d);
+                const float m = (float)(mul * a / (double)p->L);
+                const int64_t o = ((int64_t)h * p->C + c) * p->D + d;
+                if (p->q_dtype == MO_F32) ((float *)E)[o] = m;
+                else ((uint16_t *)E)[o] = f32_to_bf16_rne(m);
+            }
+        }
+    return 0;
+}
+
+/* f32 -> OCP e4m3fn, round to nearest even, saturating at +-448 (inputs are finite) */
+static uint8_t f32_to_fp8_e4m3fn_sat(float f) {
+    uint8_t s = f < 0 || (f == 0 && signbit(f)) ? 0x80 : 0;
+    double a = fabs((double)f);
+    if (a >= 448.0) return s | 0x7E;
+    if (a < ldexp(1.0, -10)) return s;                     /* below half the smallest subnormal (2^-9): zero;
+                                                              exactly 2^-10 ties to even = 0 */
+    int e;
+    (void)frexp(a, &e);                                    /* a = m * 2^e, m in [0.5,1) -> exponent e-1 */
+    int ex = e - 1;
+    if (ex < -6) ex = -6;                                  /* subnormal range shares the exponent -6 */
+    double q = ldexp(a, 3 - ex);                           /* units of the last mantissa bit */
+    double r = nearbyint(q);                               /* default rounding mode: to nearest even */
+    if (ex == -6 && r < 8) return s | (uint8_t)r;          /* subnormal (or rounds up to the first normal below) */
+    if (r >= 16) { r = 8; ex += 1; }                       /* mantissa overflow */
+    if (ex > 8 || (ex == 8 && r > 14)) return s | 0x7E;
+    return s | (uint8_t)(((ex + 7) << 3) | ((int)r - 8));
+}
+
+/* Per (chunk, KV head): scale = amax/448 (f32 division), y = x/scale (f32 division), stored as
+ * e4m3fn.  X [C,Hkv,L,D] in the q dtype (f32 or bf16).  An all-zero block gets scale 1e-30. */
+int mo_quantize_fp8(const mo_problem *p, const void *X, uint8_t *X8, float *scale) {
+    for (int c = 0; c < p->C; ++c)
+        for (int h = 0; h < p->Hkv; ++h) {
+            const int64_t base = ((int64_t)c * p->Hkv + h) * p->L * p->D, n = (int64_t)p->L * p->D;
+            float amax = 0.f;
+            for (int64_t i = 0; i < n; ++i) {
+                float v = fabsf((float)load_as_f64(p->q_dtype, X, base + i));
+                if (v > amax) amax = v;
+            }
+            float sc = amax / 448.0f;
+            if (sc < 1e-30f) sc = 1e-30f;
+            scale[c * p->Hkv + h] = sc;
+            for (int64_t i = 0; i < n; ++i) {
+                float y = (float)load_as_f64(p->q_dtype, X, base + i) / sc;
+                X8[base + i] = f32_to_fp8_e4m3fn_sat(y);
+            }
+        }
+    return 0;
+}

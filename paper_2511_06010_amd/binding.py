@@ -20,7 +20,7 @@ _DT = {"f32": F32, "bf16": BF16, "fp8": FP8_E4M3}
 _TORCH = {F32: torch.float32, BF16: torch.bfloat16, FP8_E4M3: torch.float8_e4m3fn}
 
 EXPORTS = ("moska_workspace_bytes", "moska_route", "moska_bucket", "moska_shared_attn", "moska_unique_attn",
-           "moska_merge", "moska_decode_step", "moska_status_string")
+           "moska_merge", "moska_decode_step", "moska_chunk_embeddings", "moska_quantize_shared", "moska_status_string")
 
 
 class MoskaError(RuntimeError):
@@ -163,6 +163,24 @@ def decode_step(p, Q, E, Ks, Vs, scale_k, scale_v, Ku, Vu, unique_len, ids, buck
         _dev(O, qd, (cp.B, cp.Hq, cp.D), "O"), _dev(LSE, torch.float32, (cp.B, cp.Hq), "LSE"),
         _dev(ws, torch.uint8, name="ws"), ctypes.c_size_t(0 if ws is None else ws.numel()), _stream())
     _check(rc, "moska_decode_step")
+
+
+def chunk_embeddings(p, Ks, scale_k, E):
+    cp = problem_t(p)
+    rc = load_library().moska_chunk_embeddings(
+        ctypes.byref(cp), _dev(Ks, _TORCH[cp.shared_kv_dtype], (cp.C, cp.Hkv, cp.L, cp.D), "Ks"),
+        _dev(scale_k, torch.float32, (cp.C, cp.Hkv), "scale_k"),
+        _dev(E, _TORCH[cp.q_dtype], (cp.Hkv, cp.C, cp.D), "E"), _stream())
+    _check(rc, "moska_chunk_embeddings")
+
+
+def quantize_shared(p, X, X8, scale):
+    cp = problem_t(p)
+    rc = load_library().moska_quantize_shared(
+        ctypes.byref(cp), _dev(X, torch.bfloat16, (cp.C, cp.Hkv, cp.L, cp.D), "X"),
+        _dev(X8, torch.float8_e4m3fn, (cp.C, cp.Hkv, cp.L, cp.D), "X8"),
+        _dev(scale, torch.float32, (cp.C, cp.Hkv), "scale"), _stream())
+    _check(rc, "moska_quantize_shared")
 
 
 class Buffers:

@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmoska.so")
 PROBE = os.path.join(PKG, "hbm_probe")
 SOURCES = ["attn_mfma_shared_bf16.hip", "attn_mfma_shared_fp8.hip", "attn_mfma.hip", "api.hip", "route.hip",
-           "bucket.hip", "attn_generic.hip", "merge.hip"]
+           "bucket.hip", "attn_generic.hip", "merge.hip", "cache_build.hip"]
 # packed-fp32 VALU forms are disabled on purpose (they have produced wrong results on the test machines)
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-parameter",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

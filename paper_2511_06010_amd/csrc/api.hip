@@ -166,4 +166,19 @@ int moska_decode_step(const moska_problem_t *p, const void *Q, const void *E, co
     return moska_merge(p, part_O, part_LSE, O, LSE, stream);
 }
 
+int moska_chunk_embeddings(const moska_problem_t *p, const void *Ks, const float *scale_k, void *E, void *stream) {
+    if (int rc = check_problem(p)) return rc;
+    if (!Ks || !E) return MOSKA_ERR_INVALID_ARG;
+    const bool fp8 = p->shared_kv_dtype == MOSKA_FP8_E4M3;
+    if (fp8 && !scale_k) return MOSKA_ERR_INVALID_ARG;
+    return launch_chunk_embeddings(*p, Ks, fp8 ? scale_k : nullptr, E, (hipStream_t)stream);
+}
+
+int moska_quantize_shared(const moska_problem_t *p, const void *X, void *X8, float *scale, void *stream) {
+    if (int rc = check_problem(p)) return rc;
+    if (!X || !X8 || !scale) return MOSKA_ERR_INVALID_ARG;
+    if (p->q_dtype != MOSKA_BF16 || p->shared_kv_dtype != MOSKA_FP8_E4M3) return MOSKA_ERR_UNSUPPORTED;
+    return launch_quantize_fp8(*p, X, X8, scale, (hipStream_t)stream);
+}
+
 }  // extern "C"

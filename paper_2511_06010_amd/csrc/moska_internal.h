@@ -78,6 +78,9 @@ int launch_unique_mfma(const moska_problem_t &p, const UniqueArgs &a, hipStream_
 int launch_merge(const moska_problem_t &p, const float *part_O, const float *part_LSE, void *O, float *LSE,
                  hipStream_t s);
 
+int launch_chunk_embeddings(const moska_problem_t &p, const void *Ks, const float *scale_k, void *E, hipStream_t s);
+int launch_quantize_fp8(const moska_problem_t &p, const void *X, void *X8, float *scale, hipStream_t s);
+
 inline int hip_status(hipError_t e) { return e == hipSuccess ? MOSKA_OK : MOSKA_ERR_HIP; }
 
 // ---- storage dtype helpers (device) ----------------------------------------------------

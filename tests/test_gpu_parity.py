@@ -146,6 +146,32 @@ def test_merge_empty_slots():
     torch.testing.assert_close(LSE[[0, 2]].cpu().double(), want_L, rtol=0, atol=1e-5)
 
 
+@pytest.mark.parametrize("dt,kv,D", [("f32", "f32", 64), ("bf16", "bf16", 128), ("bf16", "fp8", 128), ("bf16", "bf16", 48)])
+def test_chunk_embeddings_match_oracle(dt, kv, D):
+    p = P(q_dtype=dt, kv_dtype=kv, D=D, C=5, L=333, Hkv=3, Hq=6)
+    inp = generate(p, seed=31)
+    want = oracle.chunk_embeddings(p, inp.Ks, inp.scale_k)
+    d = inp.to("cuda")
+    E = torch.empty_like(d.E)
+    moska.chunk_embeddings(p, d.Ks, d.scale_k, E)
+    torch.cuda.synchronize()
+    assert torch.equal(E.cpu().view(torch.uint8), want.view(torch.uint8))
+
+
+def test_quantize_shared_matches_oracle_bit_for_bit():
+    p = P(kv_dtype="fp8", C=6, L=100, Hkv=2)
+    g = torch.Generator().manual_seed(32)
+    mag = torch.tensor([1e-3, 0.05, 1.0, 7.0, 300.0, 0.0]).view(6, 1, 1, 1)
+    X = (torch.randn(p.C, p.Hkv, p.L, p.D, generator=g) * mag).to(torch.bfloat16)
+    want8, want_s = oracle.quantize_fp8(p, X)
+    X8 = torch.empty(X.shape, dtype=torch.float8_e4m3fn, device="cuda")
+    sc = torch.empty(p.C, p.Hkv, device="cuda")
+    moska.quantize_shared(p, X.cuda(), X8, sc)
+    torch.cuda.synchronize()
+    assert torch.equal(sc.cpu(), want_s)
+    assert torch.equal(X8.cpu().view(torch.uint8), want8.view(torch.uint8))
+
+
 def test_invalid_arguments_are_rejected_before_launch():
     p = P()
     buf = moska.Buffers(p)

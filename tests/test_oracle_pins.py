@@ -328,3 +328,49 @@ def test_config0_matches_stored_oracle_values():
         assert [int(c) for c in st.ids[b, 0]] == [int(c) for c in ids[b]]
         np.testing.assert_allclose(st.O_direct[b, 0, :8].numpy(), O[b], rtol=1e-12, atol=1e-15)
         np.testing.assert_allclose(st.LSE_direct[b].numpy(), LSE[b], rtol=1e-13)
+
+
+# ------------------------------------------------------------------ offline cache construction
+
+def test_quantize_fp8_matches_torch_conversion():
+    # library rounding (torch float8_e4m3fn, round to nearest even) on a dense sweep of values,
+    # ties, subnormals and the saturation edge; the block's amax is 448 so its scale is exactly 1
+    x = torch.cat([torch.linspace(-448, 448, 100001), torch.randn(50000) * 0.01,
+                   torch.tensor([2.0 ** -10, 2.0 ** -9, 1.5 * 2.0 ** -10, 2.0 ** -10 * 1.0001, 0.0, -0.0, 447.9,
+                                 448.0, 0.0175, 0.0185, 13.0, 15.0, 17.0, 0.0009765625 * 3])])
+    n = (x.numel() + 15) // 16 * 16
+    xx = torch.zeros(n)
+    xx[:x.numel()] = x
+    xx = xx.to(torch.bfloat16)
+    p = Problem(B=1, Hq=1, Hkv=1, D=16, C=1, L=n // 16, k=1, U=0, q_dtype="bf16", kv_dtype="fp8")
+    X8, sc = oracle.quantize_fp8(p, xx.reshape(1, 1, p.L, 16))
+    assert sc.item() == 1.0
+    want = xx.float().clamp(-448, 448).to(torch.float8_e4m3fn)
+    assert torch.equal(X8.view(torch.uint8).flatten(), want.view(torch.uint8))
+
+
+def test_quantize_fp8_scales_and_roundtrip():
+    p = small(q_dtype="bf16", kv_dtype="fp8", D=16, C=3, L=40)
+    g = torch.Generator().manual_seed(21)
+    X = (torch.randn(p.C, p.Hkv, p.L, p.D, generator=g) * torch.tensor([0.01, 1.0, 300.0]).view(3, 1, 1, 1)).to(torch.bfloat16)
+    X8, sc = oracle.quantize_fp8(p, X)
+    amax = X.float().abs().amax(dim=(2, 3))
+    assert torch.equal(sc, amax / 448.0)
+    want = (X.float() / sc[:, :, None, None]).clamp(-448, 448).to(torch.float8_e4m3fn)
+    assert torch.equal(X8.view(torch.uint8), want.view(torch.uint8))
+    back = X8.float() * sc[:, :, None, None]
+    assert ((back - X.float()).abs() <= amax[:, :, None, None] * 2.0 ** -4 + 1e-12).all()   # half an ulp at the top binade
+
+
+@pytest.mark.parametrize("dt,kv", [("f32", "f32"), ("bf16", "bf16"), ("bf16", "fp8")])
+def test_chunk_embeddings_are_the_mean_key(dt, kv):
+    p = small(q_dtype=dt, kv_dtype=kv, C=4, L=37, D=32)
+    inp = generate(p, seed=22)
+    E = oracle.chunk_embeddings(p, inp.Ks, inp.scale_k)
+    K = f64(inp.Ks)
+    if inp.scale_k is not None:
+        K = K * f64(inp.scale_k)[:, :, None, None]
+    want = torch.tensor(K.mean(axis=2)).permute(1, 0, 2).to(torch.float32).to(inp.E.dtype)
+    assert torch.equal(E.view(torch.uint8), want.contiguous().view(torch.uint8))
+    # and it is what the generator ships as E
+    assert torch.equal(E.view(torch.uint8), inp.E.view(torch.uint8))
