@@ -59,6 +59,50 @@ def read_traffic(name):
     return None
 
 
+def paper_sweep(steps, warmup):
+    """Second workload: the paper's operating point (Sec. IV: fp8 store, 75 % routing sparsity,
+    batch growing to 256) at one-GPU scale -- shared and unique attention utilisation against batch
+    size, the measured counterpart of the paper's modelled Fig. 5.  One JSON line per batch."""
+    import torch
+    import paper_2511_06010_amd as moska
+    from moska_inputs import Problem, generate
+    for B in (1, 4, 16, 64, 256):
+        p = Problem(B=B, Hq=32, Hkv=8, D=128, C=64, L=4096, k=16, U=8192, kv_dtype="fp8",
+                    name=f"paper-point-b{B}")
+        inp = generate(p, seed=20251106, device="cuda")
+        buf = moska.Buffers(p)
+        moska.route(p, inp.Q, inp.E, buf.ids, None)
+        moska.bucket(p, buf.ids, buf.bucket_off, buf.bucket_items, buf.ws)
+
+        def timed(fn):
+            for _ in range(warmup):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / steps
+        ms_s = timed(lambda: moska.shared_attn(p, inp.Q, inp.Ks, inp.Vs, inp.scale_k, inp.scale_v, buf.ids,
+                                               buf.bucket_off, buf.bucket_items, buf.part_O, buf.part_LSE, buf.ws))
+        ms_u = timed(lambda: moska.unique_attn(p, inp.Q, inp.Ku, inp.Vu, inp.unique_len, buf.part_O, buf.part_LSE,
+                                               buf.ws))
+        w = algorithmic_work(p, buf.bucket_off.cpu())
+        rows = (buf.bucket_off[1:] - buf.bucket_off[:-1]).float() * p.G
+        print(json.dumps({
+            "workload": p.name, "B": B, "rows_per_bucket_mean": round(float(rows.mean()), 1),
+            "shared_ms": round(ms_s, 4), "shared_TFLOPs": round(w["shared_attn"]["flops"] / ms_s / 1e9, 1),
+            "shared_mfma_frac": round(w["shared_attn"]["flops"] / ms_s / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "shared_GBs": round(w["shared_attn"]["bytes"] / ms_s / 1e6, 1),
+            "shared_hbm_frac": round(w["shared_attn"]["bytes"] / ms_s / 1e6 / HBM_PEAK_GBS, 4),
+            "unique_ms": round(ms_u, 4), "unique_GBs": round(w["unique_attn"]["bytes"] / ms_u / 1e6, 1),
+            "unique_hbm_frac": round(w["unique_attn"]["bytes"] / ms_u / 1e6 / HBM_PEAK_GBS, 4),
+            "unique_mfma_frac": round(w["unique_attn"]["flops"] / ms_u / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}), flush=True)
+        del inp, buf
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -67,6 +111,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload index (2 = the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="requests in the oracle's sample (0 = auto)")
+    ap.add_argument("--paper-sweep", action="store_true",
+                    help="instead of the benchmark line: utilisation against batch size at the paper's operating point")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no sharding or collectives are part of it); use --gpus 1",
@@ -78,6 +124,11 @@ def main():
     from moska_inputs import config, generate
 
     moska.load_library()                       # fails loudly if the HIP library is not built
+    if args.paper_sweep:
+        assert torch.cuda.is_available(), "bench.py needs a GPU"
+        torch.cuda.set_device(0)
+        paper_sweep(args.steps, args.warmup)
+        return
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     p = config(args.config)
