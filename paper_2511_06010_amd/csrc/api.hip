@@ -26,6 +26,18 @@ SharedPlan shared_plan(const moska_problem_t &p) {
     return pl;
 }
 
+int unique_splits(const moska_problem_t &p) {
+    if (!use_mfma_path(p)) return 1;
+    const int G = p.Hq / p.Hkv;
+    const int rows_per_wg = G <= 16 ? 16 : G <= 32 ? 32 : 64;
+    const int64_t wgs = (int64_t)p.B * p.Hkv * ((G + rows_per_wg - 1) / rows_per_wg);
+    if (wgs >= 512 || p.U_max < 512) return 1;
+    int64_t n = (1024 + wgs - 1) / wgs;                     // aim at ~1024 workgroups ...
+    if (n > p.U_max / 256) n = p.U_max / 256;               // ... of at least 256 keys each
+    if (n > 32) n = 32;
+    return n < 1 ? 1 : (int)n;
+}
+
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 Workspace carve_workspace(const moska_problem_t &p, void *ws) {
@@ -40,6 +52,10 @@ Workspace carve_workspace(const moska_problem_t &p, void *ws) {
     w.rank = (int32_t *)(base + o);     o += align_up(items * sizeof(int32_t));
     w.off = (int32_t *)(base + o);      o += align_up((nb + 1) * sizeof(int32_t));
     w.items = (int32_t *)(base + o);    o += align_up(items * sizeof(int32_t));
+    const int ns = unique_splits(p);
+    const size_t srows = ns > 1 ? (size_t)p.B * p.Hq * ns : 0;
+    w.split_O = (float *)(base + o);    o += align_up(srows * p.D * sizeof(float));
+    w.split_LSE = (float *)(base + o);  o += align_up(srows * sizeof(float));
     w.bytes = o;
     return w;
 }
@@ -133,9 +149,15 @@ int moska_unique_attn(const moska_problem_t *p, const void *Q, const void *Ku, c
     if (int rc = check_problem(p)) return rc;
     if (!Q || !part_O || !part_LSE) return MOSKA_ERR_INVALID_ARG;
     if (p->U_max > 0 && (!Ku || !Vu)) return MOSKA_ERR_INVALID_ARG;
-    (void)ws;
-    (void)ws_bytes;
-    UniqueArgs a{Q, Ku, Vu, unique_len, part_O, part_LSE};
+    const int ns = unique_splits(*p);
+    UniqueArgs a{Q, Ku, Vu, unique_len, part_O, part_LSE, nullptr, nullptr, ns};
+    if (ns > 1) {
+        if (!ws) return MOSKA_ERR_INVALID_ARG;
+        const Workspace w = carve_workspace(*p, ws);
+        if (ws_bytes < w.bytes) return MOSKA_ERR_WORKSPACE_TOO_SMALL;
+        a.split_O = w.split_O;
+        a.split_LSE = w.split_LSE;
+    }
     hipStream_t s = (hipStream_t)stream;
     return use_mfma_path(*p) ? launch_unique_mfma(*p, a, s) : launch_unique_generic(*p, a, s);
 }

@@ -466,12 +466,16 @@ __global__ __launch_bounds__(NW * 64, min_waves(NR)) void shared_mfma_kernel(Sha
                                        scale, comb);
 }
 
+// Unique KV Attention: a workgroup serves the (up to 16*NR) query heads of one (request, KV head)
+// pair over one of nsplit contiguous slices of the request's context (nsplit = 1: all of it, the
+// result goes straight to slot k; otherwise to the split workspace, combined afterwards).
 template <int NR, int NW, int AUX, int NKB>
 __global__ __launch_bounds__(NW * 64, min_waves(NR)) void unique_mfma_kernel(UniqueArgs a, int Hq, int Hkv, int U, int k,
-                                                               float scale) {
+                                                                              float scale) {
     __shared__ float comb[(NW / 2) * 16 * NR * OSTRIDE];
-    const int G = Hq / Hkv, gt = (G + 16 * NR - 1) / (16 * NR);
-    const int bh = blockIdx.x / gt, g0 = (blockIdx.x % gt) * 16 * NR;
+    const int G = Hq / Hkv, gt = (G + 16 * NR - 1) / (16 * NR), ns = a.nsplit;
+    const int sp = blockIdx.x % ns, wg = blockIdx.x / ns;
+    const int bh = wg / gt, g0 = (wg % gt) * 16 * NR;
     const int b = bh / Hkv, h = bh - b * Hkv;
     const int lane = threadIdx.x & 63, q = lane >> 4, x = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps tile indices in SGPRs
@@ -482,15 +486,18 @@ __global__ __launch_bounds__(NW * 64, min_waves(NR)) void unique_mfma_kernel(Uni
         const int g = g0 + 16 * rb + x;
         const bool valid = g < G;
         const int64_t row = (int64_t)b * Hq + h * G + (valid ? g : 0);
-        orow[rb] = valid ? row * (k + 1) + k : -1;
+        orow[rb] = !valid ? -1 : ns > 1 ? row * ns + sp : row * (k + 1) + k;
         load_q<MOSKA_BF16>(qf[rb], a.Q, row * HD, valid, q);
     }
-    const int nkeys = a.unique_len ? min(max(a.unique_len[b], 0), U) : U;
-    const int64_t base = ((int64_t)b * Hkv + h) * U * row_bytes<MOSKA_BF16>();
+    const int len = a.unique_len ? min(max(a.unique_len[b], 0), U) : U;
+    const int per = ((len + ns - 1) / ns + 31) & ~31;       // keys per slice, whole 32-key tiles
+    const int k0 = min(sp * per, len), nkeys = min(per, len - k0);
+    const int64_t base = (((int64_t)b * Hkv + h) * U + k0) * row_bytes<MOSKA_BF16>();
     WaveState<NR> st;
     attend<NR, MOSKA_BF16, NW, AUX, NKB>(st, qf, (const char *)a.Ku + base, (const char *)a.Vu + base, nkeys,
                                          scale * kLog2e, wave, q, x);
-    combine_and_store<NR, NW>(st, comb, wave, q, x, orow, 1.f, a.part_O, a.part_LSE);
+    combine_and_store<NR, NW>(st, comb, wave, q, x, orow, 1.f, ns > 1 ? a.split_O : a.part_O,
+                              ns > 1 ? a.split_LSE : a.part_LSE);
 }
 
 // Tuning variant of a kernel instantiation: row blocks, waves per workgroup, load cache policy,

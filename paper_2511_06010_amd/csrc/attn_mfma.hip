@@ -13,6 +13,41 @@ int launch_shared_mfma(const moska_problem_t &p, const SharedArgs &a, const Shar
                                                : launch_shared_mfma_bf16(p, a, pl, s);
 }
 
+namespace {
+using mfma::HD;
+
+// Log-sum-exp combination of the nsplit slices of a split unique attention into slot k.
+// One thread per (row, 4 dims).
+__global__ __launch_bounds__(256) void unique_split_combine_kernel(UniqueArgs a, int64_t rows, int k) {
+    const int t = threadIdx.x & 31;                         // 32 threads x 4 dims = HD
+    const int64_t r = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);
+    if (r >= rows) return;
+    const int ns = a.nsplit;
+    const float *lse = a.split_LSE + r * ns;
+    float m = -INFINITY;
+    for (int s = 0; s < ns; ++s) m = fmaxf(m, lse[s]);
+    float wsum = 0.f;
+    float4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (m != -INFINITY) {
+        for (int s = 0; s < ns; ++s) {
+            const float ls = lse[s];
+            if (ls == -INFINITY) continue;
+            const float w = expf(ls - m);
+            wsum += w;
+            const float4 o = *(const float4 *)(a.split_O + (r * ns + s) * HD + 4 * t);
+            acc.x = fmaf(w, o.x, acc.x); acc.y = fmaf(w, o.y, acc.y);
+            acc.z = fmaf(w, o.z, acc.z); acc.w = fmaf(w, o.w, acc.w);
+        }
+    }
+    const float inv = wsum > 0.f ? 1.f / wsum : 0.f;
+    acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+    const int64_t o = r * (k + 1) + k;
+    *(float4 *)(a.part_O + o * HD + 4 * t) = acc;
+    if (t == 0) a.part_LSE[o] = wsum > 0.f ? m + logf(wsum) : -INFINITY;
+}
+
+}  // namespace
+
 int launch_unique_mfma(const moska_problem_t &p, const UniqueArgs &a, hipStream_t s) {
     using namespace mfma;
     struct UniqueVariant {
@@ -38,12 +73,18 @@ int launch_unique_mfma(const moska_problem_t &p, const UniqueArgs &a, hipStream_
             ++seen;
         }
     const int gt = (G + 16 * NR - 1) / (16 * NR);
-    const unsigned grid = (unsigned)((int64_t)p.B * p.Hkv * gt);
+    const unsigned grid = (unsigned)((int64_t)p.B * p.Hkv * gt * a.nsplit);
     UniqueArgs args = a;
     int Hq = p.Hq, Hkv = p.Hkv, U = p.U_max, k = p.k;
     float scale = p.scale;
     void *kargs[] = {&args, &Hq, &Hkv, &U, &k, &scale};
-    return hip_status(hipLaunchKernel(pick->kernel, dim3(grid), dim3(pick->v.NW * 64), kargs, 0, s));
+    if (hipLaunchKernel(pick->kernel, dim3(grid), dim3(pick->v.NW * 64), kargs, 0, s) != hipSuccess) return MOSKA_ERR_HIP;
+    if (a.nsplit > 1) {
+        const int64_t rows = (int64_t)p.B * p.Hq;
+        hipLaunchKernelGGL(unique_split_combine_kernel, dim3((unsigned)((rows + 7) / 8)), dim3(256), 0, s, args, rows, p.k);
+        return hip_status(hipGetLastError());
+    }
+    return MOSKA_OK;
 }
 
 }  // namespace moska

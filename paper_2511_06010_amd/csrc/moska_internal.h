@@ -40,6 +40,10 @@ inline int64_t max_tiles(const moska_problem_t &p, const SharedPlan &pl) {
     return t;
 }
 
+// Unique KV Attention splits each request's context over this many workgroups when there are too
+// few (request, KV head) pairs to fill the chip (small batches); 1 = no split.
+int unique_splits(const moska_problem_t &p);
+
 // Workspace layout (int32 units), one region per user:
 //   [tile header 8: start of each class in the tile list, total][tile list 2*Tmax]
 //   [bucket rank scratch n_items][internal bucket_off NB+1][internal bucket_items n_items]
@@ -49,6 +53,8 @@ struct Workspace {
     int32_t *rank;          // moska_bucket scratch
     int32_t *off;           // bucket_off when the caller passes none
     int32_t *items;
+    float *split_O;         // [B,Hq,splits,D] partial outputs of a split unique attention
+    float *split_LSE;       // [B,Hq,splits]
     size_t bytes;
 };
 Workspace carve_workspace(const moska_problem_t &p, void *ws);
@@ -70,6 +76,8 @@ struct UniqueArgs {
     const void *Q, *Ku, *Vu;
     const int32_t *unique_len;
     float *part_O, *part_LSE;
+    float *split_O, *split_LSE;   // workspace of a split run (nsplit > 1)
+    int nsplit;
 };
 int launch_shared_generic(const moska_problem_t &p, const SharedArgs &a, const SharedPlan &pl, hipStream_t s);
 int launch_unique_generic(const moska_problem_t &p, const UniqueArgs &a, hipStream_t s);

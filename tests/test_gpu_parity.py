@@ -36,6 +36,9 @@ SMALL = {
     "bf16-u0": P(B=6, U=0),
     "bf16-tiny-L": P(B=6, L=5, U=3),
     "bf16-scale": P(B=10, scale=0.37),
+    # few (request, KV head) pairs and a long unique context: the context is split over workgroups
+    "bf16-split-unique": P(B=2, Hq=8, Hkv=2, C=4, L=64, k=2, U=3000),
+    "bf16-split-unique-ragged": P(B=3, Hq=16, Hkv=2, C=4, L=64, k=1, U=2500),
     # bf16 with a head size the MFMA kernels do not cover (vector-ALU path)
     "bf16-d64": P(D=64, B=10, L=150, U=90),
     # fp8 shared store
