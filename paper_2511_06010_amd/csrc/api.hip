@@ -26,8 +26,18 @@ SharedPlan shared_plan(const moska_problem_t &p) {
     return pl;
 }
 
+// tuning override: a positive integer in the named environment variable replaces the heuristic
+static int env_splits(const char *name, int limit) {
+    const char *e = std::getenv(name);
+    if (!e) return 0;
+    const int v = std::atoi(e);
+    return v < 1 ? 0 : v > limit ? limit : v;
+}
+
 int unique_splits(const moska_problem_t &p) {
     if (!use_mfma_path(p)) return 1;
+    static const int forced = env_splits("MOSKA_UNIQUE_SPLITS", 32);
+    if (forced) return p.U_max >= 64 * forced ? forced : 1;
     const int G = p.Hq / p.Hkv;
     const int rows_per_wg = G <= 16 ? 16 : G <= 32 ? 32 : 64;
     const int64_t wgs = (int64_t)p.B * p.Hkv * ((G + rows_per_wg - 1) / rows_per_wg);
@@ -35,6 +45,19 @@ int unique_splits(const moska_problem_t &p) {
     int64_t n = (1024 + wgs - 1) / wgs;                     // aim at ~1024 workgroups ...
     if (n > p.U_max / 256) n = p.U_max / 256;               // ... of at least 256 keys each
     if (n > 32) n = 32;
+    return n < 1 ? 1 : (int)n;
+}
+
+int shared_splits(const moska_problem_t &p) {
+    if (!use_mfma_path(p)) return 1;
+    static const int forced = env_splits("MOSKA_SHARED_SPLITS", 16);
+    if (forced) return p.L >= 64 * forced ? forced : 1;
+    const int64_t items = (int64_t)p.B * p.Hkv * p.k, nb = (int64_t)p.Hkv * p.C;
+    const int64_t nbe = items < nb ? items : nb;            // buckets that can be non-empty
+    if (nbe > 256 || p.L < 1024) return 1;                  // one workgroup per compute unit already
+    int64_t n = (512 + nbe - 1) / nbe;                      // aim at ~512 workgroups ...
+    if (n > p.L / 512) n = p.L / 512;                       // ... of at least 512 keys each
+    if (n > 16) n = 16;
     return n < 1 ? 1 : (int)n;
 }
 
@@ -56,6 +79,10 @@ Workspace carve_workspace(const moska_problem_t &p, void *ws) {
     const size_t srows = ns > 1 ? (size_t)p.B * p.Hq * ns : 0;
     w.split_O = (float *)(base + o);    o += align_up(srows * p.D * sizeof(float));
     w.split_LSE = (float *)(base + o);  o += align_up(srows * sizeof(float));
+    const int nss = shared_splits(p);
+    const size_t ssrows = nss > 1 ? (size_t)p.B * p.Hq * p.k * nss : 0;
+    w.ssplit_O = (float *)(base + o);   o += align_up(ssrows * p.D * sizeof(float));
+    w.ssplit_LSE = (float *)(base + o); o += align_up(ssrows * sizeof(float));
     w.bytes = o;
     return w;
 }
@@ -139,7 +166,9 @@ int moska_shared_attn(const moska_problem_t *p, const void *Q, const void *Ks, c
     }
     const SharedPlan pl = shared_plan(*p);
     if (int rc = launch_tile_list(*p, bucket_off, pl, w.tile_hdr, w.tiles, s)) return rc;
-    SharedArgs a{Q, Ks, Vs, scale_k, scale_v, bucket_off, bucket_items, w.tile_hdr, w.tiles, part_O, part_LSE};
+    const int nss = shared_splits(*p);
+    SharedArgs a{Q, Ks, Vs, scale_k, scale_v, bucket_off, bucket_items, w.tile_hdr, w.tiles, part_O, part_LSE,
+                 nss > 1 ? w.ssplit_O : nullptr, nss > 1 ? w.ssplit_LSE : nullptr, nss};
     return use_mfma_path(*p) ? launch_shared_mfma(*p, a, pl, s) : launch_shared_generic(*p, a, pl, s);
 }
 

@@ -405,8 +405,22 @@ __device__ __forceinline__ void load_q(uint32_t (&qf)[4][4], const void *Q, int6
     }
 }
 
+// Slice sp of nsplit of a chunk's L keys, in whole multiples of `gran` keys: first key and count.
+__device__ __forceinline__ void key_slice(int L, int nsplit, int sp, int gran, int &k0, int &nk) {
+    const int per = ((L + nsplit - 1) / nsplit + gran - 1) / gran * gran;
+    k0 = min(sp * per, L);
+    nk = min(per, L - k0);
+}
+
+// Where a shared-attention row goes: slot j of row bh, or slice sp of that slot in the split
+// workspace (combined afterwards by shared_split_combine_kernel).
+__device__ __forceinline__ int64_t shared_out_row(const SharedArgs &a, int64_t bh, int j, int k, int sp) {
+    return a.nsplit > 1 ? (bh * k + j) * a.nsplit + sp : bh * (k + 1) + j;
+}
+
 // Tile (bkt, row0) of Shared KV Attention on the streaming path: up to 16*NR gathered rows of
-// bucket bkt against its chunk.  comb: LDS for the cross-wave merge, (NW/2)*16*NR*OSTRIDE floats.
+// bucket bkt against (slice blockIdx.y of) its chunk.  comb: LDS for the cross-wave merge,
+// (NW/2)*16*NR*OSTRIDE floats.
 template <int NR, int KVD, int NW, int AUX, int NKB>
 __device__ __forceinline__ void stream_tile(const SharedArgs &a, int bkt, int row0, int Hq, int Hkv, int C, int L,
                                             int k, float scale, float *comb) {
@@ -428,17 +442,20 @@ __device__ __forceinline__ void stream_tile(const SharedArgs &a, int bkt, int ro
             const int b = item / k, j = item - b * k;
             const int64_t bh = (int64_t)b * Hq + h * G + g;
             qoff = bh * HD;
-            orow[rb] = bh * (k + 1) + j;
+            orow[rb] = shared_out_row(a, bh, j, k, blockIdx.y);
         }
         load_q<KVD>(qf[rb], a.Q, qoff, valid, q);
     }
     const float kmul = a.scale_k ? a.scale_k[c * Hkv + h] : 1.f;
     const float vmul = a.scale_v ? a.scale_v[c * Hkv + h] : 1.f;
-    const int64_t base = ((int64_t)c * Hkv + h) * L * row_bytes<KVD>();
+    int k0, nk;
+    key_slice(L, a.nsplit, blockIdx.y, 32, k0, nk);
+    const int64_t base = (((int64_t)c * Hkv + h) * L + k0) * row_bytes<KVD>();
     WaveState<NR> st;
-    attend<NR, KVD, NW, AUX, NKB>(st, qf, (const char *)a.Ks + base, (const char *)a.Vs + base, L,
+    attend<NR, KVD, NW, AUX, NKB>(st, qf, (const char *)a.Ks + base, (const char *)a.Vs + base, nk,
                                   scale * kmul * kLog2e, wave, q, x);
-    combine_and_store<NR, NW>(st, comb, wave, q, x, orow, vmul, a.part_O, a.part_LSE);
+    combine_and_store<NR, NW>(st, comb, wave, q, x, orow, vmul, a.nsplit > 1 ? a.split_O : a.part_O,
+                              a.nsplit > 1 ? a.split_LSE : a.part_LSE);
 }
 
 // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of the tile

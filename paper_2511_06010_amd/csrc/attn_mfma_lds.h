@@ -131,6 +131,8 @@ template <int KT> constexpr int lds_units() { return 4 * KT * 16; }
 template <int NR, int NWV, int KVD, int AUX, int KT, int PD>
 __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0, int Hq, int Hkv, int C, int L, int k,
                                          float scale, uint4 *smem) {
+    int bkt_key0 = 0;                                      // first key of this workgroup's slice
+    const int Lfull = L;
     static_assert(KT == 32 || KT == 64, "keys per stage");
     static_assert(PD == 1 || PD == 2 || PD == 4, "stages in flight");
     constexpr int T = NWV * 64;
@@ -154,14 +156,20 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
             const int b = item / k, j = item - b * k;
             const int64_t bh = (int64_t)b * Hq + h * G + g;
             qoff = bh * HD;
-            orow[rb] = bh * (k + 1) + j;
+            orow[rb] = shared_out_row(a, bh, j, k, blockIdx.y);
         }
         load_q<MOSKA_BF16>(qf[rb], a.Q, qoff, valid, q);    // keys sit in LDS as bf16 in natural dim order
+    }
+    {   // this workgroup's slice of the chunk (all of it unless the chunks are split over workgroups)
+        int k0, nk;
+        key_slice(L, a.nsplit, blockIdx.y, KT, k0, nk);
+        L = nk;
+        bkt_key0 = k0;
     }
     const float kmul = a.scale_k ? a.scale_k[c * Hkv + h] : 1.f;
     const float vmul = a.scale_v ? a.scale_v[c * Hkv + h] : 1.f;
     const float sc = scale * kmul * kLog2e;
-    const int64_t base = ((int64_t)c * Hkv + h) * L * row_bytes<KVD>();
+    const int64_t base = (((int64_t)c * Hkv + h) * Lfull + bkt_key0) * row_bytes<KVD>();
     const __amdgpu_buffer_rsrc_t rk = key_set_rsrc((const char *)a.Ks + base, (uint32_t)L * row_bytes<KVD>());
     const __amdgpu_buffer_rsrc_t rv = key_set_rsrc((const char *)a.Vs + base, (uint32_t)L * row_bytes<KVD>());
 
@@ -222,7 +230,8 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
     for (int rb = 0; rb < NR; ++rb) {
         st.l[rb] = row_lanes_sum(st.l[rb]);
     }
-    store_rows<NR, true>(st, q, orow, vmul, a.part_O, a.part_LSE);
+    store_rows<NR, true>(st, q, orow, vmul, a.nsplit > 1 ? a.split_O : a.part_O,
+                         a.nsplit > 1 ? a.split_LSE : a.part_LSE);
 }
 
 constexpr int lds_min_waves(int NR) { return NR >= 4 ? 1 : 2; }
@@ -244,7 +253,7 @@ __global__ __launch_bounds__(NWV * 64, lds_min_waves(NR)) void shared_lds_kernel
 // from its end: the largest tiles start first.
 constexpr int MIXED_KT = 64;       // keys per LDS stage of the mixed launch (64 KiB of stages per workgroup)
 
-template <int KVD, int AUX>
+template <int KVD, int AUX, int PD1>
 __global__ __launch_bounds__(256, 2) void shared_mixed_kernel(SharedArgs a, int c0, int c1, int Hq, int Hkv, int C,
                                                                int L, int k, float scale) {
     __shared__ uint4 smem[lds_units<MIXED_KT>()];           // K/V stages, or the 33 KiB merge buffer
@@ -256,12 +265,24 @@ __global__ __launch_bounds__(256, 2) void shared_mixed_kernel(SharedArgs a, int 
     const int bkt = a.tiles[2 * t], row0 = a.tiles[2 * t + 1];
     int cls = c0;
     while (cls < c1 && t >= a.tile_hdr[cls + 1]) ++cls;
-    if (cls == 0) stream_tile<1, KVD, 4, AUX, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
-    else if (cls == 1) stream_tile<2, KVD, 4, AUX, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
-    else {
-        if (cls == 2) lds_tile<1, 4, KVD, AUX, MIXED_KT, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
-        else lds_tile<2, 4, KVD, AUX, MIXED_KT, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
-    }
+    // Tiles of up to 32 rows: an fp8 store streams them (each wave its own keys, twice the bytes in
+    // flight of an fp8 LDS stage); a bf16 store is faster through LDS like the 64-row tiles.
+    if (KVD == MOSKA_FP8_E4M3 && cls == 0) stream_tile<1, KVD, 4, AUX, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
+    else if (KVD == MOSKA_FP8_E4M3 && cls == 1) stream_tile<2, KVD, 4, AUX, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
+    else if (cls <= 2) lds_tile<1, 4, KVD, AUX, MIXED_KT, PD1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
+    else lds_tile<2, 4, KVD, AUX, MIXED_KT, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
+}
+
+// Classes [c0, c1] of at most 64 rows, every tile on the LDS-staged path with 16 rows per wave.
+template <int KVD, int AUX, int KT, int PD, int MINW>
+__global__ __launch_bounds__(256, MINW) void shared_small_kernel(SharedArgs a, int c0, int c1, int Hq, int Hkv, int C,
+                                                                  int L, int k, float scale) {
+    __shared__ uint4 smem[lds_units<KT>()];
+    const int first = a.tile_hdr[c0], end = a.tile_hdr[c1 + 1];
+    const int w = xcd_tile_index(end - first);
+    if (w < 0) return;
+    const int t = end - 1 - w;
+    lds_tile<1, 4, KVD, AUX, KT, PD>(a, a.tiles[2 * t], a.tiles[2 * t + 1], Hq, Hkv, C, L, k, scale, smem);
 }
 
 }  // namespace mfma

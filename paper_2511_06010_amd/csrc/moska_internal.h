@@ -43,6 +43,9 @@ inline int64_t max_tiles(const moska_problem_t &p, const SharedPlan &pl) {
 // Unique KV Attention splits each request's context over this many workgroups when there are too
 // few (request, KV head) pairs to fill the chip (small batches); 1 = no split.
 int unique_splits(const moska_problem_t &p);
+// Likewise Shared KV Attention splits every chunk's keys over this many workgroups when there are
+// too few buckets (few chunks and KV heads); 1 = no split.
+int shared_splits(const moska_problem_t &p);
 
 // Workspace layout (int32 units), one region per user:
 //   [tile header 8: start of each class in the tile list, total][tile list 2*Tmax]
@@ -55,6 +58,8 @@ struct Workspace {
     int32_t *items;
     float *split_O;         // [B,Hq,splits,D] partial outputs of a split unique attention
     float *split_LSE;       // [B,Hq,splits]
+    float *ssplit_O;        // [B,Hq,k,splits,D] partial outputs of a split shared attention
+    float *ssplit_LSE;      // [B,Hq,k,splits]
     size_t bytes;
 };
 Workspace carve_workspace(const moska_problem_t &p, void *ws);
@@ -71,6 +76,8 @@ struct SharedArgs {
     const float *scale_k, *scale_v;
     const int32_t *off, *items, *tile_hdr, *tiles;
     float *part_O, *part_LSE;
+    float *split_O, *split_LSE;   // workspace of a split run (nsplit > 1)
+    int nsplit;
 };
 struct UniqueArgs {
     const void *Q, *Ku, *Vu;

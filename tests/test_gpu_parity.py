@@ -39,6 +39,10 @@ SMALL = {
     # few (request, KV head) pairs and a long unique context: the context is split over workgroups
     "bf16-split-unique": P(B=2, Hq=8, Hkv=2, C=4, L=64, k=2, U=3000),
     "bf16-split-unique-ragged": P(B=3, Hq=16, Hkv=2, C=4, L=64, k=1, U=2500),
+    # few buckets of long chunks: every chunk is split over workgroups (all tile classes)
+    "bf16-split-shared": P(B=12, Hq=8, Hkv=2, C=4, L=2500, k=2, U=40),
+    "bf16-split-shared-hot": P(B=200, Hq=16, Hkv=2, C=2, L=1536, k=1, U=16),
+    "fp8-split-shared": P(kv_dtype="fp8", B=40, Hq=16, Hkv=2, C=3, L=1100, k=2, U=30),
     # bf16 with a head size the MFMA kernels do not cover (vector-ALU path)
     "bf16-d64": P(D=64, B=10, L=150, U=90),
     # fp8 shared store
