@@ -55,6 +55,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // round t
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+
 // Reductions over the four lanes x, x+16, x+32, x+48 that share a query row, on the vector ALU
 // (v_permlane16_swap / v_permlane32_swap hand every lane both members of its xor-16 / xor-32 pair).
 __device__ __forceinline__ float row_lanes_max(float v) {
@@ -190,40 +191,91 @@ __device__ __forceinline__ void qk_tile(f32x4 (&s)[NR][2], const uint32_t (&qf)[
 template <int NR, bool TAIL>
 __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)[NR][2], uint32_t (&pf)[NR][4],
                                              int key0, int nkeys, float sc, int q) {
+    // The reference point of a row moves only when the tile's maximum exceeds it by more than kLazy
+    // (a factor 2^kLazy in the probabilities, harmless in fp32 sums and in bf16's exponent range);
+    // otherwise nothing is rescaled.  First tile: m = -inf, always moves.
+    if constexpr (NR <= 2) {
+        // all row blocks' maxima first, then ONE wave-uniform branch around the rescale of all of them
+        float v[NR][8], mx[NR];
+        bool moved[NR], any_moved = false;
 #pragma unroll
-    for (int rb = 0; rb < NR; ++rb) {
-        float v[8];
+        for (int rb = 0; rb < NR; ++rb) {
 #pragma unroll
-        for (int kblk = 0; kblk < 2; ++kblk)
+            for (int kblk = 0; kblk < 2; ++kblk)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                float z = s[rb][kblk][r];
-                if (TAIL && key0 + 16 * kblk + 4 * q + r >= nkeys) z = -INFINITY;   // rows past the end read as 0
-                v[4 * kblk + r] = z;
+                for (int r = 0; r < 4; ++r) {
+                    float z = s[rb][kblk][r];
+                    if (TAIL && key0 + 16 * kblk + 4 * q + r >= nkeys) z = -INFINITY;   // rows past the end read as 0
+                    v[rb][4 * kblk + r] = z;
+                }
+            const float *w = v[rb];
+            mx[rb] = fmaxf(fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])), fmaxf(fmaxf(w[4], w[5]), fmaxf(w[6], w[7])));
+            mx[rb] = row_lanes_max(mx[rb]) * sc;
+            moved[rb] = mx[rb] > st.m[rb] + kLazy;
+            any_moved |= moved[rb];
+        }
+        if (__any(any_moved)) {
+#pragma unroll
+            for (int rb = 0; rb < NR; ++rb) {
+                const float mn = moved[rb] ? mx[rb] : st.m[rb];
+                const float alpha = __builtin_amdgcn_exp2f(st.m[rb] - mn);   // exactly 1 for rows that stay
+                st.m[rb] = mn;
+                st.l[rb] *= alpha;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) st.o[rb][e][r] *= alpha;
             }
-        float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
-        mx = row_lanes_max(mx) * sc;
-        // The reference point of a row moves only when the tile's maximum exceeds it by more than
-        // kLazy (a factor 2^kLazy in the probabilities, harmless in fp32 sums and in bf16's
-        // exponent range); otherwise alpha is exactly 1 and the accumulators are left alone.
-        const float mn = mx > st.m[rb] + kLazy ? mx : st.m[rb];   // first tile: m = -inf, always moves; finite after
-        const float alpha = __builtin_amdgcn_exp2f(st.m[rb] - mn);  // exactly 1 unless the reference moved
-        st.m[rb] = mn;
-        float sum = 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            v[i] = __builtin_amdgcn_exp2f(fmaf(v[i], sc, -mn));
-            sum += v[i];
         }
-        st.l[rb] = st.l[rb] * alpha + sum;
-        if (__any(alpha != 1.f)) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) st.o[rb][e] *= alpha;
+        for (int rb = 0; rb < NR; ++rb) {
+            const float mn = st.m[rb];
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                v[rb][i] = __builtin_amdgcn_exp2f(fmaf(v[rb][i], sc, -mn));
+                sum += v[rb][i];
+            }
+            st.l[rb] += sum;
+            pf[rb][0] = pack_bf16(v[rb][0], v[rb][1]);
+            pf[rb][1] = pack_bf16(v[rb][2], v[rb][3]);
+            pf[rb][2] = pack_bf16(v[rb][4], v[rb][5]);
+            pf[rb][3] = pack_bf16(v[rb][6], v[rb][7]);
         }
-        pf[rb][0] = pack_bf16(v[0], v[1]);
-        pf[rb][1] = pack_bf16(v[2], v[3]);
-        pf[rb][2] = pack_bf16(v[4], v[5]);
-        pf[rb][3] = pack_bf16(v[6], v[7]);
+    } else {
+        // four row blocks: one at a time, to keep the live scores within the register file
+#pragma unroll
+        for (int rb = 0; rb < NR; ++rb) {
+            float v[8];
+#pragma unroll
+            for (int kblk = 0; kblk < 2; ++kblk)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float z = s[rb][kblk][r];
+                    if (TAIL && key0 + 16 * kblk + 4 * q + r >= nkeys) z = -INFINITY;   // rows past the end read as 0
+                    v[4 * kblk + r] = z;
+                }
+            float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+            mx = row_lanes_max(mx) * sc;
+            const float mn = mx > st.m[rb] + kLazy ? mx : st.m[rb];   // first tile: m = -inf, always moves; finite after
+            const float alpha = __builtin_amdgcn_exp2f(st.m[rb] - mn);  // exactly 1 unless the reference moved
+            st.m[rb] = mn;
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                v[i] = __builtin_amdgcn_exp2f(fmaf(v[i], sc, -mn));
+                sum += v[i];
+            }
+            st.l[rb] = st.l[rb] * alpha + sum;
+            if (__any(alpha != 1.f)) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) st.o[rb][e] *= alpha;
+            }
+            pf[rb][0] = pack_bf16(v[0], v[1]);
+            pf[rb][1] = pack_bf16(v[2], v[3]);
+            pf[rb][2] = pack_bf16(v[4], v[5]);
+            pf[rb][3] = pack_bf16(v[6], v[7]);
+        }
     }
 }
 
