@@ -71,7 +71,7 @@ def paper_sweep(steps, warmup):
                     name=f"paper-point-b{B}")
         inp = generate(p, seed=20251106, device="cuda")
         buf = moska.Buffers(p)
-        moska.route(p, inp.Q, inp.E, buf.ids, None)
+        moska.route(p, inp.Q, inp.E, buf.ids, None, buf.ws)
         moska.bucket(p, buf.ids, buf.bucket_off, buf.bucket_items, buf.ws)
 
         def timed(fn):
@@ -141,7 +141,7 @@ def main():
     def step(events=None):
         rec = (lambda i: events[i].record()) if events is not None else (lambda i: None)
         rec(0)
-        moska.route(p, inp.Q, inp.E, buf.ids, None)
+        moska.route(p, inp.Q, inp.E, buf.ids, None, buf.ws)
         rec(1)
         moska.bucket(p, buf.ids, buf.bucket_off, buf.bucket_items, buf.ws)
         rec(2)

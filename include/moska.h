@@ -67,9 +67,9 @@ typedef struct {
     float scale;                /* logit scale, > 0 */
 } moska_problem_t;
 
-/* Bytes of device workspace that moska_bucket, moska_shared_attn and moska_unique_attn
- * may need for this problem (one buffer of this size serves all three when they run on
- * one stream).  out: host pointer. */
+/* Bytes of device workspace that moska_route, moska_bucket, moska_shared_attn and
+ * moska_unique_attn may need for this problem (one buffer of this size serves all of them
+ * when they run on one stream).  out: host pointer. */
 int moska_workspace_bytes(const moska_problem_t *p, size_t *out);
 
 /* Router (Sec. III-B).  score[b,h,c] = (sum over the G query heads of group h of Q[b,hq,:])
@@ -77,9 +77,10 @@ int moska_workspace_bytes(const moska_problem_t *p, size_t *out);
  * (score descending, chunk id ascending).
  *   Q [B,Hq,D] q_dtype, E [Hkv,C,D] q_dtype (precomputed chunk embeddings),
  *   ids [B,Hkv,k] int32 out, scores [B,Hkv,k] f32 out or NULL (scores of the selected).
+ * ws: moska_workspace_bytes (holds all B*Hkv*C scores between scoring and selection).
  * Supports C + D <= 16384. */
 int moska_route(const moska_problem_t *p, const void *Q, const void *E,
-                int32_t *ids, float *scores, void *stream);
+                int32_t *ids, float *scores, void *ws, size_t ws_bytes, void *stream);
 
 /* Query aggregation (Sec. III-A).  Item (b,h,j) -- slot j of request b on KV head h -- has
  * index b*k+j and falls into bucket h*C + ids[b,h,j].

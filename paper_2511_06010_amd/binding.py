@@ -85,13 +85,14 @@ def workspace_bytes(p) -> int:
     return out.value
 
 
-def route(p, Q, E, ids, scores=None):
+def route(p, Q, E, ids, scores, ws):
     cp = problem_t(p)
     qd = _TORCH[cp.q_dtype]
     rc = load_library().moska_route(
         ctypes.byref(cp), _dev(Q, qd, (cp.B, cp.Hq, cp.D), "Q"), _dev(E, qd, (cp.Hkv, cp.C, cp.D), "E"),
         _dev(ids, torch.int32, (cp.B, cp.Hkv, cp.k), "ids"),
-        _dev(scores, torch.float32, (cp.B, cp.Hkv, cp.k), "scores"), _stream())
+        _dev(scores, torch.float32, (cp.B, cp.Hkv, cp.k), "scores"),
+        _dev(ws, torch.uint8, name="ws"), ctypes.c_size_t(0 if ws is None else ws.numel()), _stream())
     _check(rc, "moska_route")
 
 

@@ -83,6 +83,7 @@ Workspace carve_workspace(const moska_problem_t &p, void *ws) {
     const size_t ssrows = nss > 1 ? (size_t)p.B * p.Hq * p.k * nss : 0;
     w.ssplit_O = (float *)(base + o);   o += align_up(ssrows * p.D * sizeof(float));
     w.ssplit_LSE = (float *)(base + o); o += align_up(ssrows * sizeof(float));
+    w.route_keys = (uint64_t *)(base + o); o += align_up((size_t)p.B * p.Hkv * p.C * sizeof(uint64_t));
     w.bytes = o;
     return w;
 }
@@ -131,10 +132,13 @@ int moska_workspace_bytes(const moska_problem_t *p, size_t *out) {
     return MOSKA_OK;
 }
 
-int moska_route(const moska_problem_t *p, const void *Q, const void *E, int32_t *ids, float *scores, void *stream) {
+int moska_route(const moska_problem_t *p, const void *Q, const void *E, int32_t *ids, float *scores, void *ws,
+                size_t ws_bytes, void *stream) {
     if (int rc = check_problem(p)) return rc;
-    if (!Q || !E || !ids) return MOSKA_ERR_INVALID_ARG;
-    return launch_route(*p, Q, E, ids, scores, (hipStream_t)stream);
+    if (!Q || !E || !ids || !ws) return MOSKA_ERR_INVALID_ARG;
+    const Workspace w = carve_workspace(*p, ws);
+    if (ws_bytes < w.bytes) return MOSKA_ERR_WORKSPACE_TOO_SMALL;
+    return launch_route(*p, Q, E, ids, scores, w.route_keys, (hipStream_t)stream);
 }
 
 int moska_bucket(const moska_problem_t *p, const int32_t *ids, int32_t *bucket_off, int32_t *bucket_items, void *ws,
@@ -208,7 +212,7 @@ int moska_decode_step(const moska_problem_t *p, const void *Q, const void *E, co
     if (p->U_max > 0 && (!Ku || !Vu)) return MOSKA_ERR_INVALID_ARG;
     if (p->shared_kv_dtype == MOSKA_FP8_E4M3 && (!scale_k || !scale_v)) return MOSKA_ERR_INVALID_ARG;
     if (ws_bytes < carve_workspace(*p, ws).bytes) return MOSKA_ERR_WORKSPACE_TOO_SMALL;
-    if (int rc = moska_route(p, Q, E, ids, nullptr, stream)) return rc;
+    if (int rc = moska_route(p, Q, E, ids, nullptr, ws, ws_bytes, stream)) return rc;
     if (int rc = moska_bucket(p, ids, bucket_off, bucket_items, ws, ws_bytes, stream)) return rc;
     if (int rc = moska_shared_attn(p, Q, Ks, Vs, scale_k, scale_v, ids, bucket_off, bucket_items, part_O, part_LSE, ws,
                                    ws_bytes, stream))

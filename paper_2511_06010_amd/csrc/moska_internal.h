@@ -60,11 +60,12 @@ struct Workspace {
     float *split_LSE;       // [B,Hq,splits]
     float *ssplit_O;        // [B,Hq,k,splits,D] partial outputs of a split shared attention
     float *ssplit_LSE;      // [B,Hq,k,splits]
+    uint64_t *route_keys;   // [B,Hkv,C] routing scores as order-preserving keys
     size_t bytes;
 };
 Workspace carve_workspace(const moska_problem_t &p, void *ws);
 
-int launch_route(const moska_problem_t &p, const void *Q, const void *E, int32_t *ids, float *scores,
+int launch_route(const moska_problem_t &p, const void *Q, const void *E, int32_t *ids, float *scores, uint64_t *keys,
                  hipStream_t s);
 int launch_bucket(const moska_problem_t &p, const int32_t *ids, int32_t *off, int32_t *items,
                   int32_t *rank_scratch, hipStream_t s);

@@ -1,15 +1,23 @@
 // moska_route: chunk scoring and top-k selection (paper Sec. III-B).
 //
-// One 64-lane wavefront owns one (request, KV head) pair.  Lane l scores chunks l, l+64, ...
-// against the group-summed query with fp64 FMAs (products of f32 or bf16 inputs are exact in
-// fp64, so scores agree with an fp64 reference to rounding order), turns each score into an
-// order-preserving 64-bit key kept in LDS, and the wave then extracts the k best with k rounds
-// of a butterfly arg-max over (key descending, chunk id ascending).  The work is a few MB and
-// a few GFLOP: it is launch/latency bound, far from any roofline.
+// Scoring is a dense fp64 contraction per KV head, S_h[B x C] = Qsum_h[B x D] * E_h^T[D x C], and runs
+// on the fp64 matrix cores (v_mfma_f64_16x16x4_f64): products of f32 or bf16 inputs are exact in
+// fp64, so the scores agree with an fp64 reference to the rounding order of the sums.  A wave
+// owns 16 requests of one head; the 16 x D block of group-summed queries stays in its registers as
+// the A operands while it walks over 16-chunk tiles of E, whose rows it reads with 16-byte loads
+// (the contraction index is permuted so that what a lane loads is what it feeds).  Scores leave
+// as order-preserving 64-bit keys in the workspace.
+//
+// Selection: one wave per (request, KV head) pulls its C keys into LDS and extracts the k best
+// with k rounds of a butterfly arg-max over (key descending, chunk id ascending).
+//
+// Head sizes other than 64/128/256 take a vector-ALU scoring kernel (one chunk row per lane).
 #include "moska_internal.h"
 
 namespace moska {
 namespace {
+
+typedef __attribute__((ext_vector_type(4))) double f64x4;
 
 __device__ __forceinline__ uint64_t order_key(double s) {
     s = s + 0.0;                                   // -0.0 and +0.0 must tie
@@ -26,56 +34,96 @@ __device__ __forceinline__ bool before(uint64_t ka, int ca, uint64_t kb, int cb)
     return ka > kb || (ka == kb && ca < cb);
 }
 
+// elements of a 16-byte load
+template <int QD> constexpr int epl() { return QD == MOSKA_BF16 ? 8 : 4; }
+
 template <int QD>
-__global__ __launch_bounds__(256) void route_kernel(const void *__restrict__ Q, const void *__restrict__ E,
-                                                     int32_t *__restrict__ ids, float *__restrict__ scores,
-                                                     int B, int Hq, int Hkv, int D, int C, int k, int W) {
-    extern __shared__ double smem[];
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    const int64_t rows = (int64_t)B * Hkv;
-    int64_t r = (int64_t)blockIdx.x * W + wave;    // r = h*B + b: the waves of a block share E[h]
-    const bool active = r < rows;
-    if (!active) r = rows - 1;                     // compute redundantly, write nothing
-    const int h = (int)(r / B), b = (int)(r % B), G = Hq / Hkv;
-    double *qs = smem + (size_t)wave * (D + C);
-    uint64_t *keys = (uint64_t *)(qs + D);
-
-    for (int d = lane; d < D; d += kWave) {
-        double a = 0.0;
-        for (int g = 0; g < G; ++g) a += (double)load_f32<QD>(Q, ((int64_t)b * Hq + h * G + g) * D + d);
-        qs[d] = a;
-    }
-    __syncthreads();
-
-    for (int c = lane; c < C; c += kWave) {
-        const int64_t base = ((int64_t)h * C + c) * D;
-        double a = 0.0;
-        if constexpr (QD == MOSKA_BF16) {
-            const uint4 *row = (const uint4 *)((const uint16_t *)E + base);
-            for (int d8 = 0; d8 < D / 8; ++d8) {
-                const uint4 v = row[d8];
-                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+__device__ __forceinline__ void widen16(const uint4 &v, double (&out)[epl<QD>()]) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    if constexpr (QD == MOSKA_BF16) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    a = fma(qs[d8 * 8 + 2 * i], (double)__uint_as_float(w[i] << 16), a);
-                    a = fma(qs[d8 * 8 + 2 * i + 1], (double)__uint_as_float(w[i] & 0xFFFF0000u), a);
-                }
-            }
-        } else {
-            const float4 *row = (const float4 *)((const float *)E + base);
-            for (int d4 = 0; d4 < D / 4; ++d4) {
-                const float4 v = row[d4];
-                a = fma(qs[d4 * 4 + 0], (double)v.x, a);
-                a = fma(qs[d4 * 4 + 1], (double)v.y, a);
-                a = fma(qs[d4 * 4 + 2], (double)v.z, a);
-                a = fma(qs[d4 * 4 + 3], (double)v.w, a);
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = (double)__uint_as_float(w[i] << 16);
+            out[2 * i + 1] = (double)__uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[i] = (double)__uint_as_float(w[i]);
+    }
+}
+
+// Scores of 16 requests x (a range of) 16-chunk tiles of one head, on the fp64 matrix cores.
+// D = NBLK * 4 * epl.  MFMA operands: lane (g = lane/16, x = lane%16) holds A[x][g], B[g][x] and, in
+// result register i, C[4i + g][x].  Step (blk, j) of the contraction takes dim blk*4*epl + g*epl + j from lane group
+// g, for A and B alike, so a lane's 16-byte load of a row supplies epl consecutive steps.
+template <int QD, int NBLK>
+__global__ __launch_bounds__(256) void route_score_kernel(const void *__restrict__ Q, const void *__restrict__ E,
+                                                           uint64_t *__restrict__ keys, int B, int Hq, int Hkv, int C,
+                                                           int btiles, int csplit, int ctiles) {
+    constexpr int EPL = epl<QD>(), D = NBLK * 4 * EPL, ESZ = QD == MOSKA_BF16 ? 2 : 4;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int w = blockIdx.x * 4 + wave;
+    const int cs = w % csplit, bt = (w / csplit) % btiles, h = w / (csplit * btiles);
+    if (h >= Hkv) return;
+    const int g = lane >> 4, x = lane & 15, G = Hq / Hkv;
+    const int per = (ctiles + csplit - 1) / csplit;
+    const int ct0 = cs * per, ct1 = min(ctiles, ct0 + per);
+    if (ct0 >= ct1) return;
+
+    // A operands: the group-summed query of request bt*16 + x (rows past B repeat the last one)
+    double a[NBLK * EPL];
+#pragma unroll
+    for (int i = 0; i < NBLK * EPL; ++i) a[i] = 0.0;
+    {
+        const int b = min(bt * 16 + x, B - 1);
+        const char *qrow = (const char *)Q + ((int64_t)b * Hq + (int64_t)h * G) * D * ESZ + g * 16;
+        for (int gh = 0; gh < G; ++gh) {
+#pragma unroll
+            for (int blk = 0; blk < NBLK; ++blk) {
+                double t[EPL];
+                widen16<QD>(*(const uint4 *)(qrow + ((int64_t)gh * D + blk * 4 * EPL) * ESZ), t);
+#pragma unroll
+                for (int j = 0; j < EPL; ++j) a[blk * EPL + j] += t[j];
             }
         }
-        keys[c] = order_key(a);
     }
-    __syncthreads();
 
-    // each lane remembers the best of its own chunks; only the round's winner rescans
+    const char *ebase = (const char *)E + (int64_t)h * C * D * ESZ + g * 16;
+    auto load_tile = [&](uint4 (&e)[NBLK], int ct) {
+        const int c = min(ct * 16 + x, C - 1);                 // columns past C repeat the last chunk
+        const char *row = ebase + (int64_t)c * D * ESZ;
+#pragma unroll
+        for (int blk = 0; blk < NBLK; ++blk) e[blk] = *(const uint4 *)(row + blk * 4 * EPL * ESZ);
+    };
+    uint4 e[NBLK], en[NBLK];
+    load_tile(e, ct0);
+    for (int ct = ct0; ct < ct1; ++ct) {
+        if (ct + 1 < ct1) load_tile(en, ct + 1);
+        f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int blk = 0; blk < NBLK; ++blk) {
+            double t[EPL];
+            widen16<QD>(e[blk], t);
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[blk * EPL + j], t[j], acc, 0, 0, 0);
+        }
+        const int c = ct * 16 + x;
+        if (c < C) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int b = bt * 16 + 4 * i + g;
+                if (b < B) keys[((int64_t)b * Hkv + h) * C + c] = order_key(acc[i]);
+            }
+        }
+#pragma unroll
+        for (int blk = 0; blk < NBLK; ++blk) e[blk] = en[blk];
+    }
+}
+
+// The k best of the wave's C keys (in LDS), written to ids/scores of row o = (b*Hkv + h).
+// Each lane remembers the best of its own chunks; only the round's winner rescans.
+__device__ __forceinline__ void select_topk(uint64_t *keys, int C, int k, int lane, bool active, int64_t o,
+                                            int32_t *__restrict__ ids, float *__restrict__ scores) {
     auto rescan = [&](uint64_t &bk, int &bc) {
         bk = 0;                                    // 0 is below every real key
         bc = 0x7FFFFFFF;
@@ -101,29 +149,111 @@ __global__ __launch_bounds__(256) void route_kernel(const void *__restrict__ Q, 
             rescan(bk, bc);
         }
         if (active && lane == 0) {
-            const int64_t o = ((int64_t)b * Hkv + h) * k + t;
-            ids[o] = wc;
-            if (scores) scores[o] = (float)key_to_score(wk);
+            ids[o * k + t] = wc;
+            if (scores) scores[o * k + t] = (float)key_to_score(wk);
         }
+    }
+}
+
+// One wave per (request, KV head): keys from the workspace into LDS, then the selection.
+__global__ __launch_bounds__(256) void route_select_kernel(const uint64_t *__restrict__ gkeys, int32_t *__restrict__ ids,
+                                                            float *__restrict__ scores, int64_t rows, int C, int k,
+                                                            int W) {
+    extern __shared__ double smem[];
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    int64_t r = (int64_t)blockIdx.x * W + wave;    // r = b*Hkv + h
+    const bool active = r < rows;
+    if (!active) r = rows - 1;                     // compute redundantly, write nothing
+    uint64_t *keys = (uint64_t *)smem + (size_t)wave * C;
+    for (int c = lane; c < C; c += kWave) keys[c] = gkeys[r * C + c];
+    __syncthreads();
+    select_topk(keys, C, k, lane, active, r, ids, scores);
+}
+
+// Vector-ALU scoring for the other head sizes: one wave per (request, KV head), lane l scores
+// chunks l, l+64, ... with fp64 FMAs, then the same selection.
+template <int QD>
+__global__ __launch_bounds__(256) void route_lane_kernel(const void *__restrict__ Q, const void *__restrict__ E,
+                                                          int32_t *__restrict__ ids, float *__restrict__ scores,
+                                                          int B, int Hq, int Hkv, int D, int C, int k, int W) {
+    extern __shared__ double smem[];
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int64_t rows = (int64_t)B * Hkv;
+    int64_t r = (int64_t)blockIdx.x * W + wave;    // r = h*B + b: the waves of a block share E[h]
+    const bool active = r < rows;
+    if (!active) r = rows - 1;
+    const int h = (int)(r / B), b = (int)(r % B), G = Hq / Hkv;
+    double *qs = smem + (size_t)wave * (D + C);
+    uint64_t *keys = (uint64_t *)(qs + D);
+
+    for (int d = lane; d < D; d += kWave) {
+        double a = 0.0;
+        for (int g = 0; g < G; ++g) a += (double)load_f32<QD>(Q, ((int64_t)b * Hq + h * G + g) * D + d);
+        qs[d] = a;
+    }
+    __syncthreads();
+
+    for (int c = lane; c < C; c += kWave) {
+        const int64_t base = ((int64_t)h * C + c) * D;
+        double a = 0.0;
+        for (int d = 0; d < D; ++d) a = fma(qs[d], (double)load_f32<QD>(E, base + d), a);
+        keys[c] = order_key(a);
+    }
+    __syncthreads();
+    select_topk(keys, C, k, lane, active, (int64_t)b * Hkv + h, ids, scores);
+}
+
+template <typename K>
+int raise_lds_limit(K kern, size_t lds) {
+    if (lds <= 48 * 1024) return MOSKA_OK;
+    return hip_status(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+}
+
+template <int QD>
+const void *score_kernel_for(int D) {
+    constexpr int U = 4 * epl<QD>();
+    switch (D / U) {
+    case 64 / U: return D == 64 ? (const void *)route_score_kernel<QD, 64 / U> : nullptr;
+    case 128 / U: return D == 128 ? (const void *)route_score_kernel<QD, 128 / U> : nullptr;
+    case 256 / U: return D == 256 ? (const void *)route_score_kernel<QD, 256 / U> : nullptr;
+    default: return nullptr;
     }
 }
 
 }  // namespace
 
 int launch_route(const moska_problem_t &p, const void *Q, const void *E, int32_t *ids, float *scores,
-                 hipStream_t s) {
+                 uint64_t *keys, hipStream_t s) {
+    const int64_t rows = (int64_t)p.B * p.Hkv;
+    const void *score = p.q_dtype == MOSKA_BF16 ? score_kernel_for<MOSKA_BF16>(p.D) : score_kernel_for<MOSKA_F32>(p.D);
+    if (score) {
+        int B = p.B, Hq = p.Hq, Hkv = p.Hkv, C = p.C, k = p.k;
+        int btiles = (p.B + 15) / 16, ctiles = (p.C + 15) / 16;
+        int64_t want = (4096 + (int64_t)p.Hkv * btiles - 1) / ((int64_t)p.Hkv * btiles);   // ~4096 waves
+        int csplit = (int)(want < 1 ? 1 : want > ctiles ? ctiles : want);
+        const int64_t waves = (int64_t)p.Hkv * btiles * csplit;
+        void *kargs[] = {&Q, &E, &keys, &B, &Hq, &Hkv, &C, &btiles, &csplit, &ctiles};
+        if (hipLaunchKernel(score, dim3((unsigned)((waves + 3) / 4)), dim3(256), kargs, 0, s) != hipSuccess)
+            return MOSKA_ERR_HIP;
+
+        const size_t per_wave = (size_t)p.C * sizeof(uint64_t);
+        int W = (int)((140u * 1024u) / per_wave);
+        if (W < 1) return MOSKA_ERR_UNSUPPORTED;
+        if (W > 4) W = 4;
+        const size_t lds = per_wave * W;
+        if (int rc = raise_lds_limit(route_select_kernel, lds)) return rc;
+        hipLaunchKernelGGL(route_select_kernel, dim3((unsigned)((rows + W - 1) / W)), dim3(W * kWave), lds, s,
+                           (const uint64_t *)keys, ids, scores, rows, C, k, W);
+        return hip_status(hipGetLastError());
+    }
     const size_t per_wave = (size_t)(p.D + p.C) * sizeof(double);
     int W = (int)((140u * 1024u) / per_wave);
     if (W < 1) return MOSKA_ERR_UNSUPPORTED;
     if (W > 4) W = 4;
     const size_t lds = per_wave * W;
-    const int64_t rows = (int64_t)p.B * p.Hkv;
     const unsigned grid = (unsigned)((rows + W - 1) / W);
-    auto kern = p.q_dtype == MOSKA_BF16 ? route_kernel<MOSKA_BF16> : route_kernel<MOSKA_F32>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return MOSKA_ERR_HIP;
-    }
+    auto kern = p.q_dtype == MOSKA_BF16 ? route_lane_kernel<MOSKA_BF16> : route_lane_kernel<MOSKA_F32>;
+    if (int rc = raise_lds_limit(kern, lds)) return rc;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(W * kWave), lds, s, Q, E, ids, scores, p.B, p.Hq, p.Hkv, p.D, p.C,
                        p.k, W);
     return hip_status(hipGetLastError());

@@ -79,7 +79,7 @@ def gpu_pipeline(inp: Inputs, ids_override: torch.Tensor | None = None, fused: b
         moska.decode_step(p, inp.Q, inp.E, inp.Ks, inp.Vs, inp.scale_k, inp.scale_v, inp.Ku, inp.Vu, inp.unique_len,
                           buf.ids, buf.bucket_off, buf.bucket_items, buf.part_O, buf.part_LSE, buf.O, buf.LSE, buf.ws)
     else:
-        moska.route(p, inp.Q, inp.E, buf.ids, buf.scores)
+        moska.route(p, inp.Q, inp.E, buf.ids, buf.scores, buf.ws)
         buf.routed_ids = buf.ids.clone()
         if ids_override is not None:
             buf.ids.copy_(ids_override)

@@ -43,6 +43,10 @@ SMALL = {
     "bf16-split-shared": P(B=12, Hq=8, Hkv=2, C=4, L=2500, k=2, U=40),
     "bf16-split-shared-hot": P(B=200, Hq=16, Hkv=2, C=2, L=1536, k=1, U=16),
     "fp8-split-shared": P(kv_dtype="fp8", B=40, Hq=16, Hkv=2, C=3, L=1100, k=2, U=30),
+    # head sizes 256 (widest matrix-core routing kernel) and 48 (vector-ALU routing kernel)
+    "bf16-d256": P(D=256, B=19, Hq=8, Hkv=2, C=21, L=70, k=3, U=20),
+    "f32-d256": P(q_dtype="f32", kv_dtype="f32", D=256, B=5, Hq=4, Hkv=2, C=18, L=40, k=2, U=10),
+    "bf16-d48": P(D=48, B=7, Hq=4, Hkv=2, C=10, L=50, k=2, U=12),
     # bf16 with a head size the MFMA kernels do not cover (vector-ALU path)
     "bf16-d64": P(D=64, B=10, L=150, U=90),
     # fp8 shared store
@@ -118,7 +122,7 @@ def test_route_ties_and_zero_query():
     o_ids, _, o_all = oracle.route(p, inp.Q, inp.E, want_all_scores=True)
     d = inp.to("cuda")
     ids = torch.empty_like(o_ids, device="cuda")
-    moska.route(p, d.Q, d.E, ids)
+    moska.route(p, d.Q, d.E, ids, None, moska.Buffers(p).ws)
     torch.cuda.synchronize()
     assert torch.equal(ids.cpu(), o_ids)
     assert ids[0].cpu().tolist() == [[0, 1, 2, 3]] * p.Hkv
@@ -184,7 +188,10 @@ def test_invalid_arguments_are_rejected_before_launch():
     buf = moska.Buffers(p)
     inp = generate(p, seed=1).to("cuda")
     with pytest.raises(moska.MoskaError, match="invalid"):
-        moska.route(p.with_(k=9), inp.Q, inp.E, torch.empty(p.B, p.Hkv, 9, dtype=torch.int32, device="cuda"))
+        moska.route(p.with_(k=9), inp.Q, inp.E, torch.empty(p.B, p.Hkv, 9, dtype=torch.int32, device="cuda"), None,
+                    buf.ws)
+    with pytest.raises(moska.MoskaError, match="workspace"):
+        moska.route(p, inp.Q, inp.E, buf.ids, None, buf.ws[:16])
     with pytest.raises(moska.MoskaError, match="unsupported"):
         moska.workspace_bytes(p.with_(D=72))
     with pytest.raises(moska.MoskaError, match="workspace"):

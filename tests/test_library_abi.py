@@ -46,7 +46,7 @@ def test_problem_validation_on_host():
     # null pointers are argument errors, reported before any launch
     lib = moska.load_library()
     cp = moska.problem_t(ok)
-    assert lib.moska_route(ctypes.byref(cp), None, None, None, None, None) == -1
+    assert lib.moska_route(ctypes.byref(cp), None, None, None, None, None, ctypes.c_size_t(0), None) == -1
     assert lib.moska_merge(ctypes.byref(cp), None, None, None, None, None) == -1
     assert lib.moska_workspace_bytes(None, None) == -1
 
