@@ -166,6 +166,19 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     per_call_ms = {c: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, c in enumerate(calls)}
 
+    # the same step through the single entry point (it may overlap unique attention with the rest)
+    def fused():
+        moska.decode_step(p, inp.Q, inp.E, inp.Ks, inp.Vs, inp.scale_k, inp.scale_v, inp.Ku, inp.Vu, inp.unique_len,
+                          buf.ids, buf.bucket_off, buf.bucket_items, buf.part_O, buf.part_LSE, buf.O, buf.LSE, buf.ws)
+    for _ in range(args.warmup):
+        fused()
+    torch.cuda.synchronize()
+    f0 = time.perf_counter()
+    for _ in range(args.steps):
+        fused()
+    torch.cuda.synchronize()
+    decode_step_ms = (time.perf_counter() - f0) * 1e3 / args.steps
+
     work = algorithmic_work(p, buf.bucket_off.cpu())
     kernels = {}
     for c in calls:
@@ -194,6 +207,7 @@ def main():
                    "k": p.k, "U": p.U, "shared_kv_dtype": p.kv_dtype, "popularity": p.popularity,
                    "layers": 1},
         "kernels": kernels,
+        "decode_step_ms": round(decode_step_ms, 5),
         "roofline": roofline,
     }
 
@@ -201,7 +215,7 @@ def main():
         import oracle
         from moska_inputs import Inputs
         # bounded sample: the first nb requests (all heads) against the full shared store
-        rows_per_s_guess = 25.0 * oracle.threads()                 # ~40 ms per row per core at this size
+        rows_per_s_guess = 60.0 * oracle.threads()                 # ~17 ms per row per core at this size
         nb = args.cpu_sample or max(1, min(p.B, int(15.0 * rows_per_s_guess * (36864.0 / (p.k * p.L + p.U)) / p.Hq)))
         sp = p.with_(B=nb)
         cpu = lambda t: None if t is None else t.cpu()
