@@ -46,6 +46,18 @@ def algorithmic_work(p, bucket_off):
     return w
 
 
+def shared_attainable_s(p, bucket_off):
+    """Roofline time of the shared attention for this bucket occupancy: each bucket costs the larger
+    of its HBM time (K and V once, queries in, partials out) and its MFMA time."""
+    esz_q = 4 if p.q_dtype == "f32" else 2
+    esz_kv = {"f32": 4, "bf16": 2, "fp8": 1}[p.kv_dtype]
+    rows = (bucket_off[1:] - bucket_off[:-1]).double() * p.G
+    rows = rows[rows > 0]
+    t_mem = (2 * p.L * p.D * esz_kv + rows * (p.D * esz_q + (p.D + 1) * 4)) / (HBM_PEAK_GBS * 1e9)
+    t_mfma = 4.0 * p.D * rows * p.L / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    return float(t_mem.clamp_min(t_mfma).sum())
+
+
 def read_traffic(name):
     """HBM traffic per launch measured offline with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE),
     kept as `kernel workload bytes` lines in profiles/hbm_traffic.txt; None if not recorded."""
@@ -103,6 +115,44 @@ def paper_sweep(steps, warmup):
         torch.cuda.empty_cache()
 
 
+def reuse_sweep(steps, warmup):
+    """Shared attention against query rows per bucket at the chunk shape of configs 2-4 (L = 4096,
+    D = 128, 8 KV heads, G = 4): 16 chunks, every request attends all of them (k = C), so each of the
+    128 buckets holds exactly 4*B rows.  Shows where the path leaves the HBM roofline for the MFMA
+    one (ridge: 315 rows for a bf16 store, 157 for fp8).  One JSON line per point."""
+    import torch
+    import paper_2511_06010_amd as moska
+    from moska_inputs import Problem, generate
+    for kv in ("bf16", "fp8"):
+        for B in (4, 8, 16, 32, 64, 128, 256, 512, 1024):
+            p = Problem(B=B, Hq=32, Hkv=8, D=128, C=16, L=4096, k=16, U=64, kv_dtype=kv, name=f"reuse-{kv}-m{4 * B}")
+            inp = generate(p, seed=20251106, device="cuda")
+            buf = moska.Buffers(p)
+            moska.route(p, inp.Q, inp.E, buf.ids, None, buf.ws)
+            moska.bucket(p, buf.ids, buf.bucket_off, buf.bucket_items, buf.ws)
+            fn = lambda: moska.shared_attn(p, inp.Q, inp.Ks, inp.Vs, inp.scale_k, inp.scale_v, buf.ids, buf.bucket_off,
+                                           buf.bucket_items, buf.part_O, buf.part_LSE, buf.ws)
+            for _ in range(warmup):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / steps
+            off = buf.bucket_off.cpu()
+            w = algorithmic_work(p, off)["shared_attn"]
+            att = shared_attainable_s(p, off)
+            print(json.dumps({
+                "workload": p.name, "rows_per_bucket": 4 * B, "shared_ms": round(ms, 4),
+                "TFLOPs": round(w["flops"] / ms / 1e9, 1), "mfma_frac": round(w["flops"] / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                "GBs": round(w["bytes"] / ms / 1e6, 1), "hbm_frac": round(w["bytes"] / ms / 1e6 / HBM_PEAK_GBS, 4),
+                "roofline_ms": round(att * 1e3, 4), "of_roofline": round(att * 1e3 / ms, 4)}), flush=True)
+            del inp, buf
+            torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -111,6 +161,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload index (2 = the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="requests in the oracle's sample (0 = auto)")
+    ap.add_argument("--reuse-sweep", action="store_true",
+                    help="shared attention against rows per bucket (16..4096) instead of the decode step")
     ap.add_argument("--paper-sweep", action="store_true",
                     help="instead of the benchmark line: utilisation against batch size at the paper's operating point")
     args = ap.parse_args()
@@ -124,6 +176,11 @@ def main():
     from moska_inputs import config, generate
 
     moska.load_library()                       # fails loudly if the HIP library is not built
+    if args.reuse_sweep:
+        assert torch.cuda.is_available(), "bench.py needs a GPU"
+        torch.cuda.set_device(0)
+        reuse_sweep(args.steps, args.warmup)
+        return
     if args.paper_sweep:
         assert torch.cuda.is_available(), "bench.py needs a GPU"
         torch.cuda.set_device(0)
@@ -187,6 +244,9 @@ def main():
         tfl = work[c]["flops"] / (ms * 1e-3) / 1e12
         kernels[c] = {"ms": round(ms, 5), "GB/s": round(gbs, 1), "TFLOP/s": round(tfl, 2),
                       "hbm_frac": round(gbs / HBM_PEAK_GBS, 4), "mfma_frac": round(tfl / MFMA_BF16_PEAK_TFLOPS, 4)}
+    att_s = shared_attainable_s(p, buf.bucket_off.cpu())
+    kernels["shared_attn"]["roofline_ms"] = round(att_s * 1e3, 5)          # sum over buckets of max(HBM, MFMA) time
+    kernels["shared_attn"]["of_roofline"] = round(att_s * 1e3 / per_call_ms["shared_attn"], 4)
     dom = max(("shared_attn", "unique_attn"), key=lambda c: per_call_ms[c])
     # both attention calls are bound by the bytes the method itself must stream at this workload
     # (arithmetic intensity ~ rows per bucket flop/B, far left of the 315 flop/B ridge)
