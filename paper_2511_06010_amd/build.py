@@ -19,9 +19,15 @@ FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+# The MFMA attention kernels never produce or consume a NaN (empty key sets are handled by explicit
+# -inf tests, infinities stay honoured), and saying so lets the softmax take its row maxima with
+# v_max3_f32 instead of first quieting every MFMA result (14 instead of 34 instructions per tile).
+PER_SOURCE = {s: ["-fno-honor-nans"] for s in ("attn_mfma_shared_bf16.hip", "attn_mfma_shared_fp8.hip", "attn_mfma.hip")}
+
+
 def _compile(src: str, extra) -> str:
     obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-    subprocess.check_call(["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj])
+    subprocess.check_call(["hipcc", *FLAGS, *PER_SOURCE.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj])
     return obj
 
 
