@@ -236,6 +236,19 @@ def main():
     torch.cuda.synchronize()
     decode_step_ms = (time.perf_counter() - f0) * 1e3 / args.steps
 
+    # and replayed from a HIP graph (one capture of the entry point; launch overhead off the host)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fused()
+    for _ in range(args.warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    g0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    graph_ms = (time.perf_counter() - g0) * 1e3 / args.steps
+
     work = algorithmic_work(p, buf.bucket_off.cpu())
     kernels = {}
     for c in calls:
@@ -268,6 +281,7 @@ def main():
                    "layers": 1},
         "kernels": kernels,
         "decode_step_ms": round(decode_step_ms, 5),
+        "decode_step_graph_ms": round(graph_ms, 5),
         "roofline": roofline,
     }
 

@@ -183,6 +183,48 @@ def test_quantize_shared_matches_oracle_bit_for_bit():
     assert torch.equal(X8.cpu().view(torch.uint8), want8.view(torch.uint8))
 
 
+def test_decode_step_replays_from_a_hip_graph():
+    # the five stages captured once and replayed: no call allocates, synchronises or records a
+    # memset, so a replay must give the bits of an eager run -- also after the inputs changed
+    p = P(B=24, Hq=16, Hkv=4, C=12, L=300, k=3, U=260)
+    inp = generate(p, seed=31).to("cuda")
+    other = generate(p, seed=32).to("cuda")
+    buf = moska.Buffers(p)
+
+    def step():
+        moska.decode_step(p, inp.Q, inp.E, inp.Ks, inp.Vs, inp.scale_k, inp.scale_v, inp.Ku, inp.Vu, inp.unique_len,
+                          buf.ids, buf.bucket_off, buf.bucket_items, buf.part_O, buf.part_LSE, buf.O, buf.LSE, buf.ws)
+
+    def eager_bits():
+        step()
+        torch.cuda.synchronize()
+        return buf.O.view(torch.uint8).clone(), buf.ids.clone()
+
+    want = {0: eager_bits()}
+    saved_q = inp.Q.clone()
+    inp.Q.copy_(other.Q)
+    want[1] = eager_bits()
+    inp.Q.copy_(saved_q)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                        # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for which in (0, 1, 0, 1):
+        inp.Q.copy_(other.Q if which else saved_q)      # eager work between the replays
+        buf.O.zero_()
+        buf.part_O.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(buf.O.view(torch.uint8), want[which][0]), f"replay with inputs {which}"
+        assert torch.equal(buf.ids, want[which][1])
+
+
 def test_invalid_arguments_are_rejected_before_launch():
     p = P()
     buf = moska.Buffers(p)
