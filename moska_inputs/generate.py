@@ -6,7 +6,7 @@ Recipe (one independent random stream per tensor, all derived from one seed):
   K_s[c,h,t,:]   = mu[c,h] + 0.5 N(0,1)           shared keys cluster round their centre
   V_s[c,h,t,:]   ~ N(0,1)
   c*[b]          ~ uniform, or Zipf(s) over ranks mapped through a seeded permutation
-  q[b,hq,:]      = (mu[c*[b], hq//G] + N(0,1)) / sqrt(D)
+  q[b,hq,:]      = (mu[c*[b], hq//G] + N(0,1)) / sqrt(D)     (one per query token when T > 1)
   K_u[b,h,t,:]   = mu[c*[b],h] + 0.5 N(0,1),  V_u ~ N(0,1)
   E[h,c,:]       = mean over t of the *stored* K_s[c,h,t,:]   (chunk embedding, Sec. III-B)
 
@@ -30,7 +30,7 @@ FP8_MAX = 448.0
 @dataclass
 class Inputs:
     prob: Problem
-    Q: torch.Tensor                    # [B,Hq,D]       q_dtype
+    Q: torch.Tensor                    # [B*T,Hq,D]     q_dtype (row b*T + t = token t of request b)
     E: torch.Tensor                    # [Hkv,C,D]      q_dtype
     Ks: torch.Tensor                   # [C,Hkv,L,D]    kv_dtype
     Vs: torch.Tensor                   # [C,Hkv,L,D]    kv_dtype
@@ -87,9 +87,9 @@ def generate(prob: Problem, seed: int = 20251106, device="cpu", unique_len: str 
         cstar = torch.randint(0, p.C, (p.B,), generator=g, device=dev)
 
     # queries
-    noise = _randn((p.B, p.Hq, p.D), _gen(seed, 2, dev), dev)
-    mu_q = mu[cstar]                                   # [B,Hkv,D]
-    mu_q = mu_q.repeat_interleave(G, dim=1)            # [B,Hq,D]  (head hq uses KV head hq//G)
+    noise = _randn((p.Bq, p.Hq, p.D), _gen(seed, 2, dev), dev)
+    mu_q = mu[cstar.repeat_interleave(p.T)]            # [B*T,Hkv,D]: the tokens of a request share its target
+    mu_q = mu_q.repeat_interleave(G, dim=1)            # [B*T,Hq,D]  (head hq uses KV head hq//G)
     Q = ((mu_q + noise) / math.sqrt(p.D)).to(qd)
 
     # shared store, slab by slab over chunks

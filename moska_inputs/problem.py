@@ -4,6 +4,12 @@ Notation (paper, Sec. III-A/B): B concurrent requests with one query token each,
 Hq query heads grouped G = Hq/Hkv to a KV head, head dimension D; the shared KV
 space is C chunks ("experts") of L tokens, of which the router keeps the top k per
 (request, KV head); every request also owns U tokens of unique KV.
+
+Extension (not in the paper): T = q_len query tokens per request (speculative decoding,
+chunked prefill).  Query token (b,t) is row b*T + t of Q, ids, partials and outputs; it is routed on
+its own, attends to every token of its routed chunks, and to the request's unique context up to
+and including its own position: the T new tokens are the last T of the unique_len[b] unique
+tokens, so token t sees the first unique_len[b] - (T-1-t) of them.
 """
 from __future__ import annotations
 
@@ -34,6 +40,7 @@ class Problem:
     popularity: str = "uniform"  # "uniform" or "zipf"
     zipf_s: float = 0.0
     name: str = ""
+    T: int = 1                  # query tokens per request (q_len)
 
     @property
     def G(self) -> int:
@@ -42,6 +49,10 @@ class Problem:
     @property
     def P(self) -> int:         # partial slots: k shared + 1 unique
         return self.k + 1
+
+    @property
+    def Bq(self) -> int:        # query tokens in the step
+        return self.B * self.T
 
     def with_(self, **kw) -> "Problem":
         return replace(self, **kw)

@@ -31,7 +31,7 @@ def build(force: bool = False) -> str:
 
 class _Problem(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("B", "Hq", "Hkv", "D", "C", "L", "k", "U", "q_dtype", "kv_dtype")] \
-        + [("scale", ctypes.c_double)]
+        + [("scale", ctypes.c_double), ("T", ctypes.c_int32)]
 
 
 _lib = None
@@ -48,7 +48,8 @@ def lib():
 
 
 def _cprob(p) -> _Problem:
-    return _Problem(p.B, p.Hq, p.Hkv, p.D, p.C, p.L, p.k, p.U, _DT[p.q_dtype], _DT[p.kv_dtype], float(p.scale))
+    return _Problem(p.B, p.Hq, p.Hkv, p.D, p.C, p.L, p.k, p.U, _DT[p.q_dtype], _DT[p.kv_dtype], float(p.scale),
+                    int(getattr(p, "T", 1)))
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -81,11 +82,11 @@ def widen(t: torch.Tensor) -> torch.Tensor:
 
 def route(p, Q, E, want_all_scores: bool = False):
     """S1+S2.  Returns ids [B,Hkv,k] int32, selected scores [B,Hkv,k] f64, (all scores [B,Hkv,C])."""
-    _check(Q, (p.B, p.Hq, p.D), p.q_dtype)
+    _check(Q, (p.Bq, p.Hq, p.D), p.q_dtype)
     _check(E, (p.Hkv, p.C, p.D), p.q_dtype)
-    ids = torch.empty((p.B, p.Hkv, p.k), dtype=torch.int32)
-    sel = torch.empty((p.B, p.Hkv, p.k), dtype=torch.float64)
-    allv = torch.empty((p.B, p.Hkv, p.C), dtype=torch.float64) if want_all_scores else None
+    ids = torch.empty((p.Bq, p.Hkv, p.k), dtype=torch.int32)
+    sel = torch.empty((p.Bq, p.Hkv, p.k), dtype=torch.float64)
+    allv = torch.empty((p.Bq, p.Hkv, p.C), dtype=torch.float64) if want_all_scores else None
     cp = _cprob(p)
     rc = lib().mo_route(ctypes.byref(cp), _ptr(Q), _ptr(E), _ptr(ids), _ptr(sel), _ptr(allv))
     assert rc == 0, rc
@@ -94,9 +95,9 @@ def route(p, Q, E, want_all_scores: bool = False):
 
 def bucket(p, ids):
     """Group items by (KV head, chunk).  Returns off [Hkv*C+1], items [B*Hkv*k] (int32)."""
-    _check(ids, (p.B, p.Hkv, p.k), dtype=torch.int32)
+    _check(ids, (p.Bq, p.Hkv, p.k), dtype=torch.int32)
     off = torch.empty((p.Hkv * p.C + 1,), dtype=torch.int32)
-    items = torch.empty((p.B * p.Hkv * p.k,), dtype=torch.int32)
+    items = torch.empty((p.Bq * p.Hkv * p.k,), dtype=torch.int32)
     cp = _cprob(p)
     rc = lib().mo_bucket(ctypes.byref(cp), _ptr(ids), _ptr(off), _ptr(items))
     assert rc == 0, rc
@@ -117,7 +118,7 @@ def attend(q, K, V, scale: float = 1.0):
 
 def _check_inputs(inp):
     p = inp.prob
-    _check(inp.Q, (p.B, p.Hq, p.D), p.q_dtype)
+    _check(inp.Q, (p.Bq, p.Hq, p.D), p.q_dtype)
     _check(inp.Ks, (p.C, p.Hkv, p.L, p.D), p.kv_dtype)
     _check(inp.Vs, (p.C, p.Hkv, p.L, p.D), p.kv_dtype)
     _check(inp.Ku, (p.B, p.Hkv, p.U, p.D), p.q_dtype)
@@ -132,9 +133,9 @@ def partials(inp, ids):
     """S4.  Returns part_O [B,Hq,k+1,D], part_LSE [B,Hq,k+1] (fp64)."""
     p = inp.prob
     _check_inputs(inp)
-    _check(ids, (p.B, p.Hkv, p.k), dtype=torch.int32)
-    pO = torch.empty((p.B, p.Hq, p.k + 1, p.D), dtype=torch.float64)
-    pL = torch.empty((p.B, p.Hq, p.k + 1), dtype=torch.float64)
+    _check(ids, (p.Bq, p.Hkv, p.k), dtype=torch.int32)
+    pO = torch.empty((p.Bq, p.Hq, p.k + 1, p.D), dtype=torch.float64)
+    pL = torch.empty((p.Bq, p.Hq, p.k + 1), dtype=torch.float64)
     cp = _cprob(p)
     rc = lib().mo_partials(ctypes.byref(cp), _ptr(inp.Q), _ptr(inp.Ks), _ptr(inp.Vs), _ptr(inp.scale_k),
                            _ptr(inp.scale_v), _ptr(inp.Ku), _ptr(inp.Vu), _ptr(inp.unique_len), _ptr(ids),
@@ -147,9 +148,9 @@ def direct(inp, ids):
     """S3.  Returns O [B,Hq,D], LSE [B,Hq] (fp64): attention over the routed union."""
     p = inp.prob
     _check_inputs(inp)
-    _check(ids, (p.B, p.Hkv, p.k), dtype=torch.int32)
-    O = torch.empty((p.B, p.Hq, p.D), dtype=torch.float64)
-    LSE = torch.empty((p.B, p.Hq), dtype=torch.float64)
+    _check(ids, (p.Bq, p.Hkv, p.k), dtype=torch.int32)
+    O = torch.empty((p.Bq, p.Hq, p.D), dtype=torch.float64)
+    LSE = torch.empty((p.Bq, p.Hq), dtype=torch.float64)
     cp = _cprob(p)
     rc = lib().mo_direct(ctypes.byref(cp), _ptr(inp.Q), _ptr(inp.Ks), _ptr(inp.Vs), _ptr(inp.scale_k),
                          _ptr(inp.scale_v), _ptr(inp.Ku), _ptr(inp.Vu), _ptr(inp.unique_len), _ptr(ids),

@@ -22,6 +22,11 @@
  *               reported as (O_p, LSE_p)
  *   S5 merge    log-sum-exp weighted combination of the partials    (implied by Fig. 2(b))
  *
+ * Extension (not in the paper): T = q_len query tokens per request.  Query token (b,t) is row
+ * b*T + t wherever the single-token path has row b; it is routed and attends to its shared chunks
+ * on its own, and sees the first unique_len[b] - (T-1-t) tokens of the request's unique context
+ * (the T new tokens are the last T of it: causal among themselves).  T = 1 is the paper's path.
+ *
  * Readings where the paper is silent: the G heads of a group share one selection
  * and their scores add; routing uses q unscaled; LSE is the natural log of the sum
  * of exp(scale * q.k); an empty key set yields O = 0, LSE = -inf; no mask (decode).
@@ -42,7 +47,10 @@ typedef struct {
     int32_t B, Hq, Hkv, D, C, L, k, U;
     int32_t q_dtype, kv_dtype;
     double scale;
+    int32_t T;              /* query tokens per request, >= 1 */
 } mo_problem;
+
+static int64_t query_tokens(const mo_problem *p) { return (int64_t)p->B * (p->T > 0 ? p->T : 1); }
 
 /* ---- exact widening of stored values ------------------------------------------------ */
 
@@ -99,21 +107,22 @@ static int by_score_desc_then_id(const void *a, const void *b) {
     return (x->c > y->c) - (x->c < y->c);
 }
 
-/* ids [B,Hkv,k]; sel_scores [B,Hkv,k] and all_scores [B,Hkv,C] may be NULL. */
+/* ids [B*T,Hkv,k]; sel_scores [B*T,Hkv,k] and all_scores [B*T,Hkv,C] may be NULL. */
 int mo_route(const mo_problem *p, const void *Q, const void *E,
              int32_t *ids, double *sel_scores, double *all_scores) {
     if (p->k < 1 || p->k > p->C || p->Hq % p->Hkv) return -1;
     const int G = p->Hq / p->Hkv, D = p->D, C = p->C;
-    int64_t rows = (int64_t)p->B * p->Hkv;
+    int64_t rows = query_tokens(p) * p->Hkv;
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; ++r) {
-        int b = (int)(r / p->Hkv), h = (int)(r % p->Hkv);
+        int64_t b = r / p->Hkv;                 /* query token */
+        int h = (int)(r % p->Hkv);
         double *qs = malloc(sizeof(double) * D);
         scored *sc = malloc(sizeof(scored) * C);
         for (int d = 0; d < D; ++d) {
             double a = 0.0;
             for (int g = 0; g < G; ++g)
-                a += load_as_f64(p->q_dtype, Q, ((int64_t)b * p->Hq + h * G + g) * D + d);
+                a += load_as_f64(p->q_dtype, Q, (b * p->Hq + h * G + g) * D + d);
             qs[d] = a;
         }
         for (int c = 0; c < C; ++c) {
@@ -137,26 +146,27 @@ int mo_route(const mo_problem *p, const void *Q, const void *E,
 
 /* ---- query aggregation (Sec. III-A): group routed items by (KV head, chunk) ---------- */
 
-/* Item (b,h,j) has index b*k+j inside head h and belongs to bucket h*C + ids[b,h,j].
+/* Item (b,h,j), b a query token, has index b*k+j inside head h and belongs to bucket h*C + ids[b,h,j].
  * off [Hkv*C+1] is the exclusive prefix sum of bucket sizes; items [B*Hkv*k] lists each
  * bucket's item indices in ascending order. */
 int mo_bucket(const mo_problem *p, const int32_t *ids, int32_t *off, int32_t *items) {
     const int nb = p->Hkv * p->C;
     int32_t *fill = calloc(nb + 1, sizeof(int32_t));
+    const int64_t nq = query_tokens(p);
     for (int i = 0; i <= nb; ++i) off[i] = 0;
-    for (int b = 0; b < p->B; ++b)
+    for (int64_t b = 0; b < nq; ++b)
         for (int h = 0; h < p->Hkv; ++h)
             for (int j = 0; j < p->k; ++j) {
-                int c = ids[((int64_t)b * p->Hkv + h) * p->k + j];
+                int c = ids[(b * p->Hkv + h) * p->k + j];
                 if (c < 0 || c >= p->C) { free(fill); return -1; }
                 off[h * p->C + c + 1] += 1;
             }
     for (int i = 0; i < nb; ++i) off[i + 1] += off[i];
-    for (int b = 0; b < p->B; ++b)
+    for (int64_t b = 0; b < nq; ++b)
         for (int h = 0; h < p->Hkv; ++h)
             for (int j = 0; j < p->k; ++j) {
-                int bk = h * p->C + ids[((int64_t)b * p->Hkv + h) * p->k + j];
-                items[off[bk] + fill[bk]++] = b * p->k + j;
+                int bk = h * p->C + ids[(b * p->Hkv + h) * p->k + j];
+                items[off[bk] + fill[bk]++] = (int32_t)(b * p->k + j);
             }
     free(fill);
     return 0;
@@ -226,34 +236,40 @@ static segment shared_segment(const mo_problem *p, const void *Ks, const void *V
     return s;
 }
 
+/* The unique context query token bq = b*T + t may see: the request's first len - (T-1-t) tokens. */
 static segment unique_segment(const mo_problem *p, const void *Ku, const void *Vu,
-                              const int32_t *unique_len, int b, int h) {
+                              const int32_t *unique_len, int64_t bq, int h) {
+    const int T = p->T > 0 ? p->T : 1;
+    const int64_t b = bq / T;
+    const int t = (int)(bq % T);
     segment s;
     s.dtype = p->q_dtype;
     s.K = Ku;
     s.V = Vu;
-    s.base = ((int64_t)b * p->Hkv + h) * p->U * p->D;
-    s.n = unique_len ? unique_len[b] : p->U;
+    s.base = (b * p->Hkv + h) * p->U * p->D;
+    s.n = (unique_len ? unique_len[b] : p->U) - (T - 1 - t);
+    if (s.n < 0) s.n = 0;
     s.kmul = s.vmul = 1.0;
     return s;
 }
 
 /* ---- S4: partial attentions ----------------------------------------------------------- */
 
-/* part_O [B,Hq,k+1,D], part_LSE [B,Hq,k+1]: slot j<k = chunk ids[b,h,j], slot k = unique. */
+/* part_O [B*T,Hq,k+1,D], part_LSE [B*T,Hq,k+1]: slot j<k = chunk ids[b,h,j], slot k = unique. */
 int mo_partials(const mo_problem *p, const void *Q, const void *Ks, const void *Vs,
                 const float *scale_k, const float *scale_v, const void *Ku, const void *Vu,
                 const int32_t *unique_len, const int32_t *ids, double *part_O, double *part_LSE) {
     const int G = p->Hq / p->Hkv, D = p->D, P = p->k + 1;
-    int64_t rows = (int64_t)p->B * p->Hq;
+    int64_t rows = query_tokens(p) * p->Hq;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int64_t r = 0; r < rows; ++r) {
-        int b = (int)(r / p->Hq), hq = (int)(r % p->Hq), h = hq / G;
+        int64_t b = r / p->Hq;                  /* query token */
+        int hq = (int)(r % p->Hq), h = hq / G;
         double *q = malloc(sizeof(double) * D);
         for (int d = 0; d < D; ++d) q[d] = load_as_f64(p->q_dtype, Q, r * D + d);
         for (int j = 0; j < P; ++j) {
             segment s = j < p->k
-                ? shared_segment(p, Ks, Vs, scale_k, scale_v, ids[((int64_t)b * p->Hkv + h) * p->k + j], h)
+                ? shared_segment(p, Ks, Vs, scale_k, scale_v, ids[(b * p->Hkv + h) * p->k + j], h)
                 : unique_segment(p, Ku, Vu, unique_len, b, h);
             attend_segments(D, q, p->scale, &s, 1, part_O + (r * P + j) * D, part_LSE + r * P + j);
         }
@@ -268,15 +284,16 @@ int mo_direct(const mo_problem *p, const void *Q, const void *Ks, const void *Vs
               const float *scale_k, const float *scale_v, const void *Ku, const void *Vu,
               const int32_t *unique_len, const int32_t *ids, double *O, double *LSE) {
     const int G = p->Hq / p->Hkv, D = p->D;
-    int64_t rows = (int64_t)p->B * p->Hq;
+    int64_t rows = query_tokens(p) * p->Hq;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int64_t r = 0; r < rows; ++r) {
-        int b = (int)(r / p->Hq), hq = (int)(r % p->Hq), h = hq / G;
+        int64_t b = r / p->Hq;                  /* query token */
+        int hq = (int)(r % p->Hq), h = hq / G;
         double *q = malloc(sizeof(double) * D);
         segment *seg = malloc(sizeof(segment) * (p->k + 1));
         for (int d = 0; d < D; ++d) q[d] = load_as_f64(p->q_dtype, Q, r * D + d);
         for (int j = 0; j < p->k; ++j)
-            seg[j] = shared_segment(p, Ks, Vs, scale_k, scale_v, ids[((int64_t)b * p->Hkv + h) * p->k + j], h);
+            seg[j] = shared_segment(p, Ks, Vs, scale_k, scale_v, ids[(b * p->Hkv + h) * p->k + j], h);
         seg[p->k] = unique_segment(p, Ku, Vu, unique_len, b, h);
         attend_segments(D, q, p->scale, seg, p->k + 1, O + r * D, LSE + r);
         free(q);

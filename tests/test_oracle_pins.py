@@ -374,3 +374,75 @@ def test_chunk_embeddings_are_the_mean_key(dt, kv):
     assert torch.equal(E.view(torch.uint8), want.contiguous().view(torch.uint8))
     # and it is what the generator ships as E
     assert torch.equal(E.view(torch.uint8), inp.E.view(torch.uint8))
+
+
+# ------------------------------------------------------------------ several query tokens per request
+
+def dense_reference_multi_token(inp, ids):
+    """scipy attention of every query token (b,t) and head: routed chunks in full, unique context
+    cut at the token's own position (the T new tokens are the last T unique tokens)."""
+    p = inp.prob
+    Q, Ks, Vs, Ku, Vu = map(f64, (inp.Q, inp.Ks, inp.Vs, inp.Ku, inp.Vu))
+    O = np.zeros((p.Bq, p.Hq, p.D))
+    LSE = np.full((p.Bq, p.Hq), -np.inf)
+    for b in range(p.B):
+        for t in range(p.T):
+            r = b * p.T + t
+            n = max(int(inp.unique_len[b]) - (p.T - 1 - t), 0)
+            for hq in range(p.Hq):
+                h = hq // p.G
+                sel = [int(c) for c in ids[r, h]]
+                K = np.concatenate([Ks[c, h] for c in sel] + [Ku[b, h, :n]], axis=0)
+                V = np.concatenate([Vs[c, h] for c in sel] + [Vu[b, h, :n]], axis=0)
+                z = p.scale * (K @ Q[r, hq])
+                O[r, hq] = softmax(z) @ V
+                LSE[r, hq] = logsumexp(z)
+    return O, LSE
+
+
+def test_multi_token_direct_matches_scipy_with_causal_unique_context():
+    p = small(T=3, B=4, U=9)
+    inp = generate(p, seed=41, unique_len="ragged")     # includes unique_len 0 (< T-1) and U
+    inp.unique_len[2] = 1                                # shorter than the T-1 tokens before the last one
+    st = oracle.decode_step(inp)
+    assert st.ids.shape == (p.B * p.T, p.Hkv, p.k)
+    O, LSE = dense_reference_multi_token(inp, st.ids)
+    np.testing.assert_allclose(st.O_direct.numpy(), O, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(st.LSE_direct.numpy(), LSE, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(st.O.numpy(), O, rtol=1e-10, atol=1e-12)       # merged partials
+
+
+def test_multi_token_rows_equal_single_token_problems():
+    # token t of request b == a one-token request with that query and the unique context cut there
+    p = small(T=4, B=3, U=12, k=2)
+    inp = generate(p, seed=42)
+    inp.unique_len[:] = torch.tensor([12, 7, 2], dtype=torch.int32)
+    st = oracle.decode_step(inp)
+    p1 = p.with_(T=1, B=1)
+    for b in range(p.B):
+        for t in range(p.T):
+            r = b * p.T + t
+            one = generate(p1, seed=42)
+            one.Q, one.E, one.Ks, one.Vs = inp.Q[r:r + 1].contiguous(), inp.E, inp.Ks, inp.Vs
+            one.Ku, one.Vu = inp.Ku[b:b + 1].contiguous(), inp.Vu[b:b + 1].contiguous()
+            one.unique_len = torch.tensor([max(int(inp.unique_len[b]) - (p.T - 1 - t), 0)], dtype=torch.int32)
+            s1 = oracle.decode_step(one)
+            assert torch.equal(s1.ids[0], st.ids[r])
+            np.testing.assert_allclose(st.part_O[r].numpy(), s1.part_O[0].numpy(), rtol=0, atol=0)
+            np.testing.assert_allclose(st.part_LSE[r].numpy(), s1.part_LSE[0].numpy(), rtol=0, atol=0)
+            np.testing.assert_allclose(st.O_direct[r].numpy(), s1.O_direct[0].numpy(), rtol=0, atol=0)
+
+
+def test_multi_token_bucket_items_are_token_major():
+    p = small(T=2, B=3)
+    inp = generate(p, seed=43)
+    ids, _ = oracle.route(p, inp.Q, inp.E)
+    off, items = oracle.bucket(p, ids)
+    assert off[-1] == p.B * p.T * p.Hkv * p.k
+    flat = ids.numpy()
+    for h in range(p.Hkv):
+        chunk_of_item = flat[:, h, :].reshape(-1)                       # item = (b*T + t)*k + j
+        order = np.argsort(chunk_of_item, kind="stable")
+        want = order.astype(np.int32)
+        got = items[off[h * p.C]:off[(h + 1) * p.C]].numpy()
+        assert np.array_equal(got, want)
