@@ -31,12 +31,13 @@ def algorithmic_work(p, bucket_off):
     esz_kv = {"f32": 4, "bf16": 2, "fp8": 1}[p.kv_dtype]
     sizes = (bucket_off[1:] - bucket_off[:-1])
     nonempty = int((sizes > 0).sum())
-    rows_q = p.B * p.Hq
+    Bq = p.B * p.T                      # query tokens; only the unique K/V are per request
+    rows_q = Bq * p.Hq
     shared_rows = rows_q * p.k
     w = {}
-    w["route"] = dict(bytes=p.B * p.Hq * p.D * esz_q + p.Hkv * p.C * p.D * esz_q + p.B * p.Hkv * p.k * 4,
-                      flops=2.0 * p.B * p.Hkv * p.C * p.D)
-    w["bucket"] = dict(bytes=p.B * p.Hkv * p.k * 4 * 4 + (p.Hkv * p.C + 1) * 4, flops=0.0)
+    w["route"] = dict(bytes=Bq * p.Hq * p.D * esz_q + p.Hkv * p.C * p.D * esz_q + Bq * p.Hkv * p.k * 4,
+                      flops=2.0 * Bq * p.Hkv * p.C * p.D)
+    w["bucket"] = dict(bytes=Bq * p.Hkv * p.k * 4 * 4 + (p.Hkv * p.C + 1) * 4, flops=0.0)
     w["shared_attn"] = dict(bytes=nonempty * 2 * p.L * p.D * esz_kv + shared_rows * p.D * esz_q
                             + shared_rows * (p.D + 1) * 4,
                             flops=4.0 * p.D * shared_rows * p.L)
@@ -159,6 +160,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, help="workload index (2 = the headline configuration)")
+    ap.add_argument("--q-len", type=int, default=1,
+                    help="query tokens per request: the same number of query tokens from B/q_len requests")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="requests in the oracle's sample (0 = auto)")
     ap.add_argument("--reuse-sweep", action="store_true",
@@ -189,6 +192,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     p = config(args.config)
+    if args.q_len > 1:
+        assert p.B % args.q_len == 0, "q_len must divide the batch size"
+        p = p.with_(T=args.q_len, B=p.B // args.q_len, name=p.name + f"-qlen{args.q_len}")
     inp = generate(p, seed=20251106 + args.config, device="cuda")
     buf = moska.Buffers(p)
     torch.cuda.synchronize()
@@ -270,14 +276,14 @@ def main():
 
     out = {
         "metric": "shared-attn TFLOP/s + decode queries/s, B=256, 1M shared tokens, 1 GPU",
-        "value": round(p.B / (ms_per_step * 1e-3), 1), "unit": "queries/s",
+        "value": round(p.Bq / (ms_per_step * 1e-3), 1), "unit": "queries/s",
         "shared_attn_tflops": kernels["shared_attn"]["TFLOP/s"],
         "unique_attn_gbs": kernels["unique_attn"]["GB/s"],
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if p.q_dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": p.name, "B": p.B, "Hq": p.Hq, "Hkv": p.Hkv, "D": p.D, "C": p.C, "L": p.L,
-                   "k": p.k, "U": p.U, "shared_kv_dtype": p.kv_dtype, "popularity": p.popularity,
+                   "k": p.k, "U": p.U, "q_len": p.T, "shared_kv_dtype": p.kv_dtype, "popularity": p.popularity,
                    "layers": 1},
         "kernels": kernels,
         "decode_step_ms": round(decode_step_ms, 5),
@@ -290,10 +296,11 @@ def main():
         from moska_inputs import Inputs
         # bounded sample: the first nb requests (all heads) against the full shared store
         rows_per_s_guess = 60.0 * oracle.threads()                 # ~17 ms per row per core at this size
-        nb = args.cpu_sample or max(1, min(p.B, int(15.0 * rows_per_s_guess * (36864.0 / (p.k * p.L + p.U)) / p.Hq)))
+        nb = args.cpu_sample or max(1, min(p.B, int(15.0 * rows_per_s_guess * (36864.0 / (p.k * p.L + p.U)) / p.Hq) // p.T))
         sp = p.with_(B=nb)
+        nq = nb * p.T                                               # query tokens of the sampled requests
         cpu = lambda t: None if t is None else t.cpu()
-        sub = Inputs(sp, inp.Q[:nb].cpu(), inp.E.cpu(), inp.Ks.cpu(), inp.Vs.cpu(), cpu(inp.scale_k), cpu(inp.scale_v),
+        sub = Inputs(sp, inp.Q[:nq].cpu(), inp.E.cpu(), inp.Ks.cpu(), inp.Vs.cpu(), cpu(inp.scale_k), cpu(inp.scale_v),
                      inp.Ku[:nb].cpu(), inp.Vu[:nb].cpu(), inp.unique_len[:nb].cpu(), inp.cstar[:nb].cpu())
         c0 = time.perf_counter()
         ids, _ = oracle.route(sp, sub.Q, sub.E)
@@ -301,8 +308,8 @@ def main():
         pO, pL = oracle.partials(sub, ids)
         O, _ = oracle.merge(pO, pL)
         c1 = time.perf_counter()
-        err = float((buf.O[:nb].double().cpu() - O).abs().max())
-        out["cpu_baseline"] = {"value": round(nb / (c1 - c0), 3), "unit": "queries/s", "cores": oracle.threads(),
+        err = float((buf.O[:nq].double().cpu() - O).abs().max())
+        out["cpu_baseline"] = {"value": round(nq / (c1 - c0), 3), "unit": "queries/s", "cores": oracle.threads(),
                                "kind": "oracle", "seconds": round(c1 - c0, 2),
                                "sample": f"first {nb} of {p.B} requests, all {p.Hq} heads, full shared store; "
                                          f"max |GPU-oracle| on the sample {err:.2e}"}

@@ -18,6 +18,13 @@
  * head dimension D, C shared chunks of L tokens each, top-k = k, U_max unique tokens per
  * request (request b uses the first unique_len[b]), P = k+1 partial slots per query row.
  *
+ * Several query tokens per request (q_len = T > 1; an extension beyond the paper, for speculative
+ * decoding or chunked prefill against the shared store): query token (b,t) takes the place of
+ * request b in every shape below -- read B as B*T with row b*T + t -- except in Ku, Vu and
+ * unique_len, which stay per request.  Each token is routed on its own and attends to all of its
+ * routed chunks; the T tokens are the last T of the request's unique_len[b] unique tokens, and
+ * token t attends to the first unique_len[b] - (T-1-t) of them (at least 0).
+ *
  * Conventions common to every call
  *   - `p` and `out` are HOST pointers.  Every other pointer is a DEVICE pointer owned by
  *     the caller, 16-byte aligned, dense row-major in the stated shape (last index
@@ -65,6 +72,7 @@ typedef struct {
     int32_t q_dtype;            /* MOSKA_F32 or MOSKA_BF16: dtype of Q, E, unique K/V and O */
     int32_t shared_kv_dtype;    /* MOSKA_F32 (only with q F32), MOSKA_BF16 or MOSKA_FP8_E4M3 (with q BF16) */
     float scale;                /* logit scale, > 0 */
+    int32_t q_len;              /* T, query tokens per request; 0 reads as 1 (see "Several query tokens") */
 } moska_problem_t;
 
 /* Bytes of device workspace that moska_route, moska_bucket, moska_shared_attn and

@@ -30,7 +30,12 @@ class MoskaError(RuntimeError):
 class ProblemT(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("B", "Hq", "Hkv", "D", "C", "L", "k", "U_max", "q_dtype", "shared_kv_dtype")] + \
-               [("scale", ctypes.c_float)]
+               [("scale", ctypes.c_float), ("q_len", ctypes.c_int32)]
+
+    @property
+    def Bq(self) -> int:
+        """Query tokens in the step: the leading size of Q, ids, partials and outputs."""
+        return self.B * max(self.q_len, 1)
 
 
 _lib = None
@@ -54,7 +59,8 @@ def problem_t(p) -> ProblemT:
     """moska_inputs.Problem (or anything with the same fields) -> moska_problem_t."""
     if isinstance(p, ProblemT):
         return p
-    return ProblemT(p.B, p.Hq, p.Hkv, p.D, p.C, p.L, p.k, p.U, _DT[p.q_dtype], _DT[p.kv_dtype], float(p.scale))
+    return ProblemT(p.B, p.Hq, p.Hkv, p.D, p.C, p.L, p.k, p.U, _DT[p.q_dtype], _DT[p.kv_dtype], float(p.scale),
+                    int(getattr(p, "T", 1)))
 
 
 def _check(rc: int, what: str):
@@ -89,9 +95,9 @@ def route(p, Q, E, ids, scores, ws):
     cp = problem_t(p)
     qd = _TORCH[cp.q_dtype]
     rc = load_library().moska_route(
-        ctypes.byref(cp), _dev(Q, qd, (cp.B, cp.Hq, cp.D), "Q"), _dev(E, qd, (cp.Hkv, cp.C, cp.D), "E"),
-        _dev(ids, torch.int32, (cp.B, cp.Hkv, cp.k), "ids"),
-        _dev(scores, torch.float32, (cp.B, cp.Hkv, cp.k), "scores"),
+        ctypes.byref(cp), _dev(Q, qd, (cp.Bq, cp.Hq, cp.D), "Q"), _dev(E, qd, (cp.Hkv, cp.C, cp.D), "E"),
+        _dev(ids, torch.int32, (cp.Bq, cp.Hkv, cp.k), "ids"),
+        _dev(scores, torch.float32, (cp.Bq, cp.Hkv, cp.k), "scores"),
         _dev(ws, torch.uint8, name="ws"), ctypes.c_size_t(0 if ws is None else ws.numel()), _stream())
     _check(rc, "moska_route")
 
@@ -99,9 +105,9 @@ def route(p, Q, E, ids, scores, ws):
 def bucket(p, ids, bucket_off, bucket_items, ws):
     cp = problem_t(p)
     rc = load_library().moska_bucket(
-        ctypes.byref(cp), _dev(ids, torch.int32, (cp.B, cp.Hkv, cp.k), "ids"),
+        ctypes.byref(cp), _dev(ids, torch.int32, (cp.Bq, cp.Hkv, cp.k), "ids"),
         _dev(bucket_off, torch.int32, (cp.Hkv * cp.C + 1,), "bucket_off"),
-        _dev(bucket_items, torch.int32, (cp.B * cp.Hkv * cp.k,), "bucket_items"),
+        _dev(bucket_items, torch.int32, (cp.Bq * cp.Hkv * cp.k,), "bucket_items"),
         _dev(ws, torch.uint8, name="ws"), ctypes.c_size_t(0 if ws is None else ws.numel()), _stream())
     _check(rc, "moska_bucket")
 
@@ -111,14 +117,14 @@ def shared_attn(p, Q, Ks, Vs, scale_k, scale_v, ids, bucket_off, bucket_items, p
     qd, kd = _TORCH[cp.q_dtype], _TORCH[cp.shared_kv_dtype]
     kv_shape = (cp.C, cp.Hkv, cp.L, cp.D)
     rc = load_library().moska_shared_attn(
-        ctypes.byref(cp), _dev(Q, qd, (cp.B, cp.Hq, cp.D), "Q"), _dev(Ks, kd, kv_shape, "Ks"),
+        ctypes.byref(cp), _dev(Q, qd, (cp.Bq, cp.Hq, cp.D), "Q"), _dev(Ks, kd, kv_shape, "Ks"),
         _dev(Vs, kd, kv_shape, "Vs"), _dev(scale_k, torch.float32, (cp.C, cp.Hkv), "scale_k"),
         _dev(scale_v, torch.float32, (cp.C, cp.Hkv), "scale_v"),
-        _dev(ids, torch.int32, (cp.B, cp.Hkv, cp.k), "ids"),
+        _dev(ids, torch.int32, (cp.Bq, cp.Hkv, cp.k), "ids"),
         _dev(bucket_off, torch.int32, (cp.Hkv * cp.C + 1,), "bucket_off"),
-        _dev(bucket_items, torch.int32, (cp.B * cp.Hkv * cp.k,), "bucket_items"),
-        _dev(part_O, torch.float32, (cp.B, cp.Hq, cp.k + 1, cp.D), "part_O"),
-        _dev(part_LSE, torch.float32, (cp.B, cp.Hq, cp.k + 1), "part_LSE"),
+        _dev(bucket_items, torch.int32, (cp.Bq * cp.Hkv * cp.k,), "bucket_items"),
+        _dev(part_O, torch.float32, (cp.Bq, cp.Hq, cp.k + 1, cp.D), "part_O"),
+        _dev(part_LSE, torch.float32, (cp.Bq, cp.Hq, cp.k + 1), "part_LSE"),
         _dev(ws, torch.uint8, name="ws"), ctypes.c_size_t(0 if ws is None else ws.numel()), _stream())
     _check(rc, "moska_shared_attn")
 
@@ -128,10 +134,10 @@ def unique_attn(p, Q, Ku, Vu, unique_len, part_O, part_LSE, ws):
     qd = _TORCH[cp.q_dtype]
     kv_shape = (cp.B, cp.Hkv, cp.U_max, cp.D)
     rc = load_library().moska_unique_attn(
-        ctypes.byref(cp), _dev(Q, qd, (cp.B, cp.Hq, cp.D), "Q"), _dev(Ku, qd, kv_shape, "Ku"),
+        ctypes.byref(cp), _dev(Q, qd, (cp.Bq, cp.Hq, cp.D), "Q"), _dev(Ku, qd, kv_shape, "Ku"),
         _dev(Vu, qd, kv_shape, "Vu"), _dev(unique_len, torch.int32, (cp.B,), "unique_len"),
-        _dev(part_O, torch.float32, (cp.B, cp.Hq, cp.k + 1, cp.D), "part_O"),
-        _dev(part_LSE, torch.float32, (cp.B, cp.Hq, cp.k + 1), "part_LSE"),
+        _dev(part_O, torch.float32, (cp.Bq, cp.Hq, cp.k + 1, cp.D), "part_O"),
+        _dev(part_LSE, torch.float32, (cp.Bq, cp.Hq, cp.k + 1), "part_LSE"),
         _dev(ws, torch.uint8, name="ws"), ctypes.c_size_t(0 if ws is None else ws.numel()), _stream())
     _check(rc, "moska_unique_attn")
 
@@ -139,9 +145,9 @@ def unique_attn(p, Q, Ku, Vu, unique_len, part_O, part_LSE, ws):
 def merge(p, part_O, part_LSE, O, LSE=None):
     cp = problem_t(p)
     rc = load_library().moska_merge(
-        ctypes.byref(cp), _dev(part_O, torch.float32, (cp.B, cp.Hq, cp.k + 1, cp.D), "part_O"),
-        _dev(part_LSE, torch.float32, (cp.B, cp.Hq, cp.k + 1), "part_LSE"),
-        _dev(O, _TORCH[cp.q_dtype], (cp.B, cp.Hq, cp.D), "O"), _dev(LSE, torch.float32, (cp.B, cp.Hq), "LSE"),
+        ctypes.byref(cp), _dev(part_O, torch.float32, (cp.Bq, cp.Hq, cp.k + 1, cp.D), "part_O"),
+        _dev(part_LSE, torch.float32, (cp.Bq, cp.Hq, cp.k + 1), "part_LSE"),
+        _dev(O, _TORCH[cp.q_dtype], (cp.Bq, cp.Hq, cp.D), "O"), _dev(LSE, torch.float32, (cp.Bq, cp.Hq), "LSE"),
         _stream())
     _check(rc, "moska_merge")
 
@@ -151,17 +157,17 @@ def decode_step(p, Q, E, Ks, Vs, scale_k, scale_v, Ku, Vu, unique_len, ids, buck
     cp = problem_t(p)
     qd, kd = _TORCH[cp.q_dtype], _TORCH[cp.shared_kv_dtype]
     rc = load_library().moska_decode_step(
-        ctypes.byref(cp), _dev(Q, qd, (cp.B, cp.Hq, cp.D), "Q"), _dev(E, qd, (cp.Hkv, cp.C, cp.D), "E"),
+        ctypes.byref(cp), _dev(Q, qd, (cp.Bq, cp.Hq, cp.D), "Q"), _dev(E, qd, (cp.Hkv, cp.C, cp.D), "E"),
         _dev(Ks, kd, (cp.C, cp.Hkv, cp.L, cp.D), "Ks"), _dev(Vs, kd, (cp.C, cp.Hkv, cp.L, cp.D), "Vs"),
         _dev(scale_k, torch.float32, (cp.C, cp.Hkv), "scale_k"), _dev(scale_v, torch.float32, (cp.C, cp.Hkv), "scale_v"),
         _dev(Ku, qd, (cp.B, cp.Hkv, cp.U_max, cp.D), "Ku"), _dev(Vu, qd, (cp.B, cp.Hkv, cp.U_max, cp.D), "Vu"),
         _dev(unique_len, torch.int32, (cp.B,), "unique_len"),
-        _dev(ids, torch.int32, (cp.B, cp.Hkv, cp.k), "ids"),
+        _dev(ids, torch.int32, (cp.Bq, cp.Hkv, cp.k), "ids"),
         _dev(bucket_off, torch.int32, (cp.Hkv * cp.C + 1,), "bucket_off"),
-        _dev(bucket_items, torch.int32, (cp.B * cp.Hkv * cp.k,), "bucket_items"),
-        _dev(part_O, torch.float32, (cp.B, cp.Hq, cp.k + 1, cp.D), "part_O"),
-        _dev(part_LSE, torch.float32, (cp.B, cp.Hq, cp.k + 1), "part_LSE"),
-        _dev(O, qd, (cp.B, cp.Hq, cp.D), "O"), _dev(LSE, torch.float32, (cp.B, cp.Hq), "LSE"),
+        _dev(bucket_items, torch.int32, (cp.Bq * cp.Hkv * cp.k,), "bucket_items"),
+        _dev(part_O, torch.float32, (cp.Bq, cp.Hq, cp.k + 1, cp.D), "part_O"),
+        _dev(part_LSE, torch.float32, (cp.Bq, cp.Hq, cp.k + 1), "part_LSE"),
+        _dev(O, qd, (cp.Bq, cp.Hq, cp.D), "O"), _dev(LSE, torch.float32, (cp.Bq, cp.Hq), "LSE"),
         _dev(ws, torch.uint8, name="ws"), ctypes.c_size_t(0 if ws is None else ws.numel()), _stream())
     _check(rc, "moska_decode_step")
 
@@ -190,12 +196,12 @@ class Buffers:
     def __init__(self, p, device="cuda"):
         cp = problem_t(p)
         dev = torch.device(device)
-        self.ids = torch.empty((cp.B, cp.Hkv, cp.k), dtype=torch.int32, device=dev)
-        self.scores = torch.empty((cp.B, cp.Hkv, cp.k), dtype=torch.float32, device=dev)
+        self.ids = torch.empty((cp.Bq, cp.Hkv, cp.k), dtype=torch.int32, device=dev)
+        self.scores = torch.empty((cp.Bq, cp.Hkv, cp.k), dtype=torch.float32, device=dev)
         self.bucket_off = torch.empty((cp.Hkv * cp.C + 1,), dtype=torch.int32, device=dev)
-        self.bucket_items = torch.empty((cp.B * cp.Hkv * cp.k,), dtype=torch.int32, device=dev)
-        self.part_O = torch.empty((cp.B, cp.Hq, cp.k + 1, cp.D), dtype=torch.float32, device=dev)
-        self.part_LSE = torch.empty((cp.B, cp.Hq, cp.k + 1), dtype=torch.float32, device=dev)
-        self.O = torch.empty((cp.B, cp.Hq, cp.D), dtype=_TORCH[cp.q_dtype], device=dev)
-        self.LSE = torch.empty((cp.B, cp.Hq), dtype=torch.float32, device=dev)
+        self.bucket_items = torch.empty((cp.Bq * cp.Hkv * cp.k,), dtype=torch.int32, device=dev)
+        self.part_O = torch.empty((cp.Bq, cp.Hq, cp.k + 1, cp.D), dtype=torch.float32, device=dev)
+        self.part_LSE = torch.empty((cp.Bq, cp.Hq, cp.k + 1), dtype=torch.float32, device=dev)
+        self.O = torch.empty((cp.Bq, cp.Hq, cp.D), dtype=_TORCH[cp.q_dtype], device=dev)
+        self.LSE = torch.empty((cp.Bq, cp.Hq), dtype=torch.float32, device=dev)
         self.ws = torch.empty((workspace_bytes(p),), dtype=torch.uint8, device=dev)

@@ -38,9 +38,9 @@ int unique_splits(const moska_problem_t &p) {
     if (!use_mfma_path(p)) return 1;
     static const int forced = env_splits("MOSKA_UNIQUE_SPLITS", 32);
     if (forced) return p.U_max >= 64 * forced ? forced : 1;
-    const int G = p.Hq / p.Hkv;
-    const int rows_per_wg = G <= 16 ? 16 : G <= 32 ? 32 : 64;
-    const int64_t wgs = (int64_t)p.B * p.Hkv * ((G + rows_per_wg - 1) / rows_per_wg);
+    const int R = q_len(p) * (p.Hq / p.Hkv);                   // query rows per (request, KV head)
+    const int rows_per_wg = R <= 16 ? 16 : R <= 32 ? 32 : 64;
+    const int64_t wgs = (int64_t)p.B * p.Hkv * ((R + rows_per_wg - 1) / rows_per_wg);
     if (wgs >= 512 || p.U_max < 512) return 1;
     int64_t n = (1024 + wgs - 1) / wgs;                     // aim at ~1024 workgroups ...
     if (n > p.U_max / 256) n = p.U_max / 256;               // ... of at least 256 keys each
@@ -52,7 +52,7 @@ int shared_splits(const moska_problem_t &p) {
     if (!use_mfma_path(p)) return 1;
     static const int forced = env_splits("MOSKA_SHARED_SPLITS", 16);
     if (forced) return p.L >= 64 * forced ? forced : 1;
-    const int64_t items = (int64_t)p.B * p.Hkv * p.k, nb = (int64_t)p.Hkv * p.C;
+    const int64_t items = (int64_t)p.B * q_len(p) * p.Hkv * p.k, nb = (int64_t)p.Hkv * p.C;
     const int64_t nbe = items < nb ? items : nb;            // buckets that can be non-empty
     if (nbe > 256 || p.L < 1024) return 1;                  // one workgroup per compute unit already
     int64_t n = (512 + nbe - 1) / nbe;                      // aim at ~512 workgroups ...
@@ -65,7 +65,8 @@ static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 Workspace carve_workspace(const moska_problem_t &p, void *ws) {
     Workspace w;
-    const size_t items = (size_t)p.B * p.Hkv * p.k, nb = (size_t)p.Hkv * p.C;
+    const size_t Bq = (size_t)p.B * q_len(p);               // query tokens
+    const size_t items = Bq * p.Hkv * p.k, nb = (size_t)p.Hkv * p.C;
     // bound valid for every plan: at most one remainder tile per class and bucket plus the full tiles
     const size_t tmax = (size_t)(4 * (items < nb ? items : nb) + (items * (size_t)(p.Hq / p.Hkv)) / 16 + 8);
     char *base = (char *)ws;
@@ -76,21 +77,22 @@ Workspace carve_workspace(const moska_problem_t &p, void *ws) {
     w.off = (int32_t *)(base + o);      o += align_up((nb + 1) * sizeof(int32_t));
     w.items = (int32_t *)(base + o);    o += align_up(items * sizeof(int32_t));
     const int ns = unique_splits(p);
-    const size_t srows = ns > 1 ? (size_t)p.B * p.Hq * ns : 0;
+    const size_t srows = ns > 1 ? Bq * p.Hq * ns : 0;
     w.split_O = (float *)(base + o);    o += align_up(srows * p.D * sizeof(float));
     w.split_LSE = (float *)(base + o);  o += align_up(srows * sizeof(float));
     const int nss = shared_splits(p);
-    const size_t ssrows = nss > 1 ? (size_t)p.B * p.Hq * p.k * nss : 0;
+    const size_t ssrows = nss > 1 ? Bq * p.Hq * p.k * nss : 0;
     w.ssplit_O = (float *)(base + o);   o += align_up(ssrows * p.D * sizeof(float));
     w.ssplit_LSE = (float *)(base + o); o += align_up(ssrows * sizeof(float));
-    w.route_keys = (uint64_t *)(base + o); o += align_up((size_t)p.B * p.Hkv * p.C * sizeof(uint64_t));
+    w.route_keys = (uint64_t *)(base + o); o += align_up(Bq * p.Hkv * p.C * sizeof(uint64_t));
     w.bytes = o;
     return w;
 }
 
 static int check_problem(const moska_problem_t *p) {
     if (!p) return MOSKA_ERR_INVALID_ARG;
-    if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->D < 1 || p->C < 1 || p->L < 1 || p->k < 1 || p->U_max < 0)
+    if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->D < 1 || p->C < 1 || p->L < 1 || p->k < 1 || p->U_max < 0 ||
+        p->q_len < 0)
         return MOSKA_ERR_INVALID_ARG;
     if (p->Hq % p->Hkv != 0 || p->k > p->C || !(p->scale > 0.f)) return MOSKA_ERR_INVALID_ARG;
     if (p->D % 16 != 0 || p->D > 256) return MOSKA_ERR_UNSUPPORTED;
@@ -103,8 +105,8 @@ static int check_problem(const moska_problem_t *p) {
     if ((int64_t)p->L * p->D * 4 >= (int64_t)1 << 32 || (int64_t)p->U_max * p->D * 4 >= (int64_t)1 << 32)
         return MOSKA_ERR_UNSUPPORTED;
     // index arithmetic inside one head uses int32 item numbers
-    if ((int64_t)p->B * p->Hkv * p->k > (int64_t)1 << 30 || (int64_t)p->B * p->Hq * (p->k + 1) > (int64_t)1 << 30)
-        return MOSKA_ERR_UNSUPPORTED;
+    const int64_t Bq = (int64_t)p->B * q_len(*p);
+    if (Bq * p->Hkv * p->k > (int64_t)1 << 30 || Bq * p->Hq * (p->k + 1) > (int64_t)1 << 30) return MOSKA_ERR_UNSUPPORTED;
     return MOSKA_OK;
 }
 
@@ -138,7 +140,7 @@ int moska_route(const moska_problem_t *p, const void *Q, const void *E, int32_t 
     if (!Q || !E || !ids || !ws) return MOSKA_ERR_INVALID_ARG;
     const Workspace w = carve_workspace(*p, ws);
     if (ws_bytes < w.bytes) return MOSKA_ERR_WORKSPACE_TOO_SMALL;
-    return launch_route(*p, Q, E, ids, scores, w.route_keys, (hipStream_t)stream);
+    return launch_route(per_token(*p), Q, E, ids, scores, w.route_keys, (hipStream_t)stream);
 }
 
 int moska_bucket(const moska_problem_t *p, const int32_t *ids, int32_t *bucket_off, int32_t *bucket_items, void *ws,
@@ -147,7 +149,7 @@ int moska_bucket(const moska_problem_t *p, const int32_t *ids, int32_t *bucket_o
     if (!ids || !bucket_off || !bucket_items || !ws) return MOSKA_ERR_INVALID_ARG;
     const Workspace w = carve_workspace(*p, ws);
     if (ws_bytes < w.bytes) return MOSKA_ERR_WORKSPACE_TOO_SMALL;
-    return launch_bucket(*p, ids, bucket_off, bucket_items, w.rank, (hipStream_t)stream);
+    return launch_bucket(per_token(*p), ids, bucket_off, bucket_items, w.rank, (hipStream_t)stream);
 }
 
 int moska_shared_attn(const moska_problem_t *p, const void *Q, const void *Ks, const void *Vs, const float *scale_k,
@@ -164,16 +166,17 @@ int moska_shared_attn(const moska_problem_t *p, const void *Q, const void *Ks, c
     if (ws_bytes < w.bytes) return MOSKA_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t s = (hipStream_t)stream;
     if (!bucket_off) {
-        if (int rc = launch_bucket(*p, ids, w.off, w.items, w.rank, s)) return rc;
+        if (int rc = launch_bucket(per_token(*p), ids, w.off, w.items, w.rank, s)) return rc;
         bucket_off = w.off;
         bucket_items = w.items;
     }
     const SharedPlan pl = shared_plan(*p);
-    if (int rc = launch_tile_list(*p, bucket_off, pl, w.tile_hdr, w.tiles, s)) return rc;
+    const moska_problem_t f = per_token(*p);
+    if (int rc = launch_tile_list(f, bucket_off, pl, w.tile_hdr, w.tiles, s)) return rc;
     const int nss = shared_splits(*p);
     SharedArgs a{Q, Ks, Vs, scale_k, scale_v, bucket_off, bucket_items, w.tile_hdr, w.tiles, part_O, part_LSE,
                  nss > 1 ? w.ssplit_O : nullptr, nss > 1 ? w.ssplit_LSE : nullptr, nss};
-    return use_mfma_path(*p) ? launch_shared_mfma(*p, a, pl, s) : launch_shared_generic(*p, a, pl, s);
+    return use_mfma_path(f) ? launch_shared_mfma(f, a, pl, s) : launch_shared_generic(f, a, pl, s);
 }
 
 int moska_unique_attn(const moska_problem_t *p, const void *Q, const void *Ku, const void *Vu,
@@ -199,7 +202,7 @@ int moska_merge(const moska_problem_t *p, const float *part_O, const float *part
                 void *stream) {
     if (int rc = check_problem(p)) return rc;
     if (!part_O || !part_LSE || !O) return MOSKA_ERR_INVALID_ARG;
-    return launch_merge(*p, part_O, part_LSE, O, LSE, (hipStream_t)stream);
+    return launch_merge(per_token(*p), part_O, part_LSE, O, LSE, (hipStream_t)stream);
 }
 
 int moska_decode_step(const moska_problem_t *p, const void *Q, const void *E, const void *Ks, const void *Vs,

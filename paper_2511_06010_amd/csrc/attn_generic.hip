@@ -21,7 +21,8 @@ constexpr int MAXD16 = 16;  // D <= 256
 struct RowSet {             // the rows a workgroup serves and the keys they attend to
     int nrows;
     int64_t kv_base;        // element offset of key 0 in K and V
-    int nkeys;
+    int nkeys;              // keys of the set; row r sees the first lim[r] <= nkeys of them (lim = nullptr: all)
+    const int *lim;         // LDS array
     float kmul, vmul;
 };
 
@@ -48,6 +49,7 @@ __device__ void attend_tile_rows(const RowSet &rs, const int64_t *q_off, const i
     for (int i = 0; i < MAXD16; ++i) acc[i] = 0.f;
     float m = -INFINITY, l = 0.f;
     const float sc = scale * rs.kmul;
+    const int mylim = rs.lim ? rs.lim[r] : rs.nkeys;
 
     for (int k0 = 0; k0 < rs.nkeys; k0 += TK) {
         __syncthreads();                 // previous tile fully consumed (and Qs written)
@@ -66,17 +68,17 @@ __device__ void attend_tile_rows(const RowSet &rs, const int64_t *q_off, const i
             const int kk = x + 16 * i;
             float a = 0.f;
             for (int d = 0; d < D; ++d) a = fmaf(Qs[r * DP + d], Ks[kk * DP + d], a);
-            s[i] = kk < nk ? a * sc : -INFINITY;
+            s[i] = k0 + kk < mylim ? a * sc : -INFINITY;
             tmax = fmaxf(tmax, s[i]);
         }
 #pragma unroll
         for (int w = 1; w < 16; w <<= 1) tmax = fmaxf(tmax, __shfl_xor(tmax, w, 16));
-        const float mn = fmaxf(m, tmax);             // finite: the tile has at least one key
+        const float mn = fmaxf(m, tmax);             // -inf only while the row has seen no key
         const float alpha = m == -INFINITY ? 0.f : expf(m - mn);
         float lsum = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const float pv = expf(s[i] - mn);         // exp(-inf) = 0 for masked keys
+            const float pv = s[i] == -INFINITY ? 0.f : expf(s[i] - mn);   // masked keys weigh nothing
             Ps[r * (TK + 1) + x + 16 * i] = pv;
             lsum += pv;
         }
@@ -118,6 +120,7 @@ __global__ __launch_bounds__(256) void shared_generic_kernel(SharedArgs a, int B
     rs.nrows = min(MT, rows - row0);
     rs.kv_base = ((int64_t)c * Hkv + h) * L * D;
     rs.nkeys = L;
+    rs.lim = nullptr;
     rs.kmul = a.scale_k ? a.scale_k[c * Hkv + h] : 1.f;
     rs.vmul = a.scale_v ? a.scale_v[c * Hkv + h] : 1.f;
     if (threadIdx.x < TR && (int)threadIdx.x < rs.nrows) {
@@ -131,22 +134,29 @@ __global__ __launch_bounds__(256) void shared_generic_kernel(SharedArgs a, int B
     attend_tile_rows<QD, KD>(rs, q_off, o_row, a.Q, a.Ks, a.Vs, scale, D, a.part_O, a.part_LSE, P);
 }
 
+// Rows of a (request, KV head) pair: row t*G + g is query token t, head g of the group; token t
+// sees the first len - (T-1-t) keys of the request's context.
 template <int QD>
 __global__ __launch_bounds__(256) void unique_generic_kernel(UniqueArgs a, int B, int Hq, int Hkv, int D, int U,
-                                                              int k, float scale) {
+                                                              int k, float scale, int T) {
     __shared__ int64_t q_off[TR], o_row[TR];
-    const int G = Hq / Hkv, P = k + 1, gt = (G + TR - 1) / TR;
-    const int bh = blockIdx.x / gt, g0 = (blockIdx.x % gt) * TR;
+    __shared__ int lim[TR];
+    const int G = Hq / Hkv, P = k + 1, R = T * G, gt = (R + TR - 1) / TR;
+    const int bh = blockIdx.x / gt, r0 = (blockIdx.x % gt) * TR;
     const int b = bh / Hkv, h = bh - b * Hkv;
     RowSet rs;
-    rs.nrows = min(TR, G - g0);
+    rs.nrows = min(TR, R - r0);
     rs.kv_base = ((int64_t)b * Hkv + h) * U * D;
     rs.nkeys = a.unique_len ? min(max(a.unique_len[b], 0), U) : U;
+    rs.lim = lim;
     rs.kmul = rs.vmul = 1.f;
-    if ((int)threadIdx.x < rs.nrows) {
-        const int hq = h * G + g0 + threadIdx.x;
-        q_off[threadIdx.x] = ((int64_t)b * Hq + hq) * D;
-        o_row[threadIdx.x] = ((int64_t)b * Hq + hq) * P + k;
+    if ((int)threadIdx.x < TR) {
+        const int r = min(r0 + (int)threadIdx.x, R - 1);
+        const int t = r / G, hq = h * G + (r - t * G);
+        const int64_t row = ((int64_t)b * T + t) * Hq + hq;
+        q_off[threadIdx.x] = row * D;
+        o_row[threadIdx.x] = row * P + k;
+        lim[threadIdx.x] = max(rs.nkeys - (T - 1 - t), 0);
     }
     __syncthreads();
     attend_tile_rows<QD, QD>(rs, q_off, o_row, a.Q, a.Ku, a.Vu, scale, D, a.part_O, a.part_LSE, P);
@@ -179,11 +189,11 @@ int launch_shared_generic(const moska_problem_t &p, const SharedArgs &a, const S
 
 int launch_unique_generic(const moska_problem_t &p, const UniqueArgs &a, hipStream_t s) {
     const size_t lds = generic_lds_bytes(p.D);
-    const int G = p.Hq / p.Hkv;
-    const unsigned grid = (unsigned)((int64_t)p.B * p.Hkv * ((G + TR - 1) / TR));
+    const int T = q_len(p), R = T * (p.Hq / p.Hkv);
+    const unsigned grid = (unsigned)((int64_t)p.B * p.Hkv * ((R + TR - 1) / TR));
     auto kern = p.q_dtype == MOSKA_BF16 ? unique_generic_kernel<MOSKA_BF16> : unique_generic_kernel<MOSKA_F32>;
     if (int rc = set_lds(kern, lds)) return rc;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, a, p.B, p.Hq, p.Hkv, p.D, p.U_max, p.k, p.scale);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, a, p.B, p.Hq, p.Hkv, p.D, p.U_max, p.k, p.scale, T);
     return hip_status(hipGetLastError());
 }
 

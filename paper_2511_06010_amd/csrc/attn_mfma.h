@@ -186,11 +186,21 @@ __device__ __forceinline__ void qk_tile(f32x4 (&s)[NR][2], const uint32_t (&qf)[
     }
 }
 
+// Number of keys row block rb may see: one count for all rows, or one per row block (each lane its
+// own row's), for query tokens at different positions of the same context.
+__device__ __forceinline__ int limit_of(int nkeys, int) { return nkeys; }
+template <int NR> __device__ __forceinline__ int limit_of(const int (&lim)[NR], int rb) { return lim[rb]; }
+
 // online softmax in the log2 domain; produces the P^T operands and rescales O when a max moved.
 // sc > 0 folds the logit scale, the dequantisation factor of the keys and log2(e).
-template <int NR, bool TAIL>
+// TAIL: keys at or past the row's limit are masked (a row may then have no key at all yet: its
+// reference stays -inf and its probabilities are zero).
+template <int NR, bool TAIL, typename LIM>
 __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)[NR][2], uint32_t (&pf)[NR][4],
-                                             int key0, int nkeys, float sc, int q) {
+                                             int key0, const LIM &nkeys, float sc, int q) {
+    // with one count for all rows every masked tile still holds a key of every row; with per-row
+    // counts a row may have none so far (m = -inf) and must come out of the tile unchanged
+    constexpr bool EMPTY_ROWS = TAIL && !__is_same(LIM, int);
     // The reference point of a row moves only when the tile's maximum exceeds it by more than kLazy
     // (a factor 2^kLazy in the probabilities, harmless in fp32 sums and in bf16's exponent range);
     // otherwise nothing is rescaled.  First tile: m = -inf, always moves.
@@ -205,7 +215,7 @@ __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     float z = s[rb][kblk][r];
-                    if (TAIL && key0 + 16 * kblk + 4 * q + r >= nkeys) z = -INFINITY;   // rows past the end read as 0
+                    if (TAIL && key0 + 16 * kblk + 4 * q + r >= limit_of(nkeys, rb)) z = -INFINITY;   // rows past the end read as 0
                     v[rb][4 * kblk + r] = z;
                 }
             const float *w = v[rb];
@@ -218,7 +228,8 @@ __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)
 #pragma unroll
             for (int rb = 0; rb < NR; ++rb) {
                 const float mn = moved[rb] ? mx[rb] : st.m[rb];
-                const float alpha = __builtin_amdgcn_exp2f(st.m[rb] - mn);   // exactly 1 for rows that stay
+                float alpha = __builtin_amdgcn_exp2f(st.m[rb] - mn);          // exactly 1 for rows that stay
+                if (EMPTY_ROWS && !moved[rb]) alpha = 1.f;                    // (-inf) - (-inf)
                 st.m[rb] = mn;
                 st.l[rb] *= alpha;
 #pragma unroll
@@ -229,7 +240,7 @@ __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)
         }
 #pragma unroll
         for (int rb = 0; rb < NR; ++rb) {
-            const float mn = st.m[rb];
+            const float mn = EMPTY_ROWS && st.m[rb] == -INFINITY ? 0.f : st.m[rb];   // no key yet: exp2(-inf) = 0 below
             float sum = 0.f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -252,18 +263,21 @@ __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     float z = s[rb][kblk][r];
-                    if (TAIL && key0 + 16 * kblk + 4 * q + r >= nkeys) z = -INFINITY;   // rows past the end read as 0
+                    if (TAIL && key0 + 16 * kblk + 4 * q + r >= limit_of(nkeys, rb)) z = -INFINITY;   // rows past the end read as 0
                     v[4 * kblk + r] = z;
                 }
             float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
             mx = row_lanes_max(mx) * sc;
-            const float mn = mx > st.m[rb] + kLazy ? mx : st.m[rb];   // first tile: m = -inf, always moves; finite after
-            const float alpha = __builtin_amdgcn_exp2f(st.m[rb] - mn);  // exactly 1 unless the reference moved
+            const bool moved = mx > st.m[rb] + kLazy;                  // first tile with a key: m = -inf, moves
+            const float mn = moved ? mx : st.m[rb];
+            float alpha = __builtin_amdgcn_exp2f(st.m[rb] - mn);       // exactly 1 unless the reference moved
+            if (EMPTY_ROWS && !moved) alpha = 1.f;                     // (-inf) - (-inf)
             st.m[rb] = mn;
+            const float off = EMPTY_ROWS && mn == -INFINITY ? 0.f : mn;   // no key yet: exp2(-inf) = 0 below
             float sum = 0.f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                v[i] = __builtin_amdgcn_exp2f(fmaf(v[i], sc, -mn));
+                v[i] = __builtin_amdgcn_exp2f(fmaf(v[i], sc, -off));
                 sum += v[i];
             }
             st.l[rb] = st.l[rb] * alpha + sum;
@@ -308,9 +322,12 @@ __device__ __forceinline__ void pv_tile(WaveState<NR> &st, const TileV<KVD> &t, 
 // no branch).  NKB = 1: one key tile and one value tile in flight per wave, latency hidden by the
 // other waves of the SIMD.  NKB = 2: two key tiles in flight, for the 64-row kernels whose
 // register footprint allows only one wave per SIMD.
-template <int NR, int KVD, int NW, int AUX, int NKB>
+// lim: how many of the keys each row may see -- nkeys itself (an int), or per row block the lane's
+// own row's count (<= nkeys); nsafe <= every row's count: tiles below it need no masking.
+template <int NR, int KVD, int NW, int AUX, int NKB, typename LIM>
 __device__ __forceinline__ void attend(WaveState<NR> &st, const uint32_t (&qf)[NR][4][4], const char *Kb,
-                                       const char *Vb, int nkeys, float sc, int wave, int q, int x) {
+                                       const char *Vb, int nkeys, int nsafe, const LIM &lim, float sc, int wave,
+                                       int q, int x) {
     static_assert(NKB == 1 || NKB == 2, "key tiles in flight");
 #pragma unroll
     for (int rb = 0; rb < NR; ++rb) {
@@ -319,7 +336,7 @@ __device__ __forceinline__ void attend(WaveState<NR> &st, const uint32_t (&qf)[N
 #pragma unroll
         for (int e = 0; e < 8; ++e) st.o[rb][e] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    const int nfull = nkeys >> 5;                  // tiles without a ragged end
+    const int nfull = nsafe >> 5;                  // tiles that every row sees whole
     const LaneOff<KVD> lo(q, x);
     const __amdgpu_buffer_rsrc_t rk = key_set_rsrc(Kb, (uint32_t)nkeys * row_bytes<KVD>());
     const __amdgpu_buffer_rsrc_t rv = key_set_rsrc(Vb, (uint32_t)nkeys * row_bytes<KVD>());
@@ -354,11 +371,13 @@ __device__ __forceinline__ void attend(WaveState<NR> &st, const uint32_t (&qf)[N
             } while (t < nfull);
         }
     }
-    if ((nkeys & 31) && (nfull % NW) == wave) {    // the ragged last tile belongs to one wave
-        load_k<KVD, AUX>(tk[0], rk, lo, nfull);
-        load_v<KVD, AUX>(tv, rv, lo, nfull);
+    // the remaining tiles (one ragged tile; a few when the rows' counts differ) are masked per row
+    const int ntiles = (nkeys + 31) >> 5;
+    for (int tt = nfull + ((wave - nfull % NW + NW) % NW); tt < ntiles; tt += NW) {
+        load_k<KVD, AUX>(tk[0], rk, lo, tt);
+        load_v<KVD, AUX>(tv, rv, lo, tt);
         qk_tile<NR, KVD>(s, qf, tk[0]);
-        softmax_tile<NR, true>(st, s, pf, 32 * nfull, nkeys, sc, q);
+        softmax_tile<NR, true>(st, s, pf, 32 * tt, lim, sc, q);
         pv_tile<NR, KVD>(st, tv, pf);
     }
 }
@@ -504,7 +523,7 @@ __device__ __forceinline__ void stream_tile(const SharedArgs &a, int bkt, int ro
     key_slice(L, a.nsplit, blockIdx.y, 32, k0, nk);
     const int64_t base = (((int64_t)c * Hkv + h) * L + k0) * row_bytes<KVD>();
     WaveState<NR> st;
-    attend<NR, KVD, NW, AUX, NKB>(st, qf, (const char *)a.Ks + base, (const char *)a.Vs + base, nk,
+    attend<NR, KVD, NW, AUX, NKB>(st, qf, (const char *)a.Ks + base, (const char *)a.Vs + base, nk, nk, nk,
                                   scale * kmul * kLog2e, wave, q, x);
     combine_and_store<NR, NW>(st, comb, wave, q, x, orow, vmul, a.nsplit > 1 ? a.split_O : a.part_O,
                               a.nsplit > 1 ? a.split_LSE : a.part_LSE);
@@ -535,35 +554,42 @@ __global__ __launch_bounds__(NW * 64, min_waves(NR)) void shared_mfma_kernel(Sha
                                        scale, comb);
 }
 
-// Unique KV Attention: a workgroup serves the (up to 16*NR) query heads of one (request, KV head)
-// pair over one of nsplit contiguous slices of the request's context (nsplit = 1: all of it, the
-// result goes straight to slot k; otherwise to the split workspace, combined afterwards).
+// Unique KV Attention: a workgroup serves (up to 16*NR of) the T*G query rows of one (request, KV
+// head) pair -- row t*G + g is query token t, head g of the group -- over one of nsplit contiguous
+// slices of the request's context (nsplit = 1: all of it, the result goes straight to slot k;
+// otherwise to the split workspace, combined afterwards).  Token t sees the first len - (T-1-t) keys.
 template <int NR, int NW, int AUX, int NKB>
 __global__ __launch_bounds__(NW * 64, min_waves(NR)) void unique_mfma_kernel(UniqueArgs a, int Hq, int Hkv, int U, int k,
-                                                                              float scale) {
+                                                                              float scale, int T) {
     __shared__ float comb[(NW / 2) * 16 * NR * OSTRIDE];
-    const int G = Hq / Hkv, gt = (G + 16 * NR - 1) / (16 * NR), ns = a.nsplit;
+    const int G = Hq / Hkv, R = T * G, gt = (R + 16 * NR - 1) / (16 * NR), ns = a.nsplit;
     const int sp = blockIdx.x % ns, wg = blockIdx.x / ns;
-    const int bh = wg / gt, g0 = (wg % gt) * 16 * NR;
+    const int bh = wg / gt, r0 = (wg % gt) * 16 * NR;
     const int b = bh / Hkv, h = bh - b * Hkv;
     const int lane = threadIdx.x & 63, q = lane >> 4, x = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps tile indices in SGPRs
-    uint32_t qf[NR][4][4];
-    int64_t orow[NR];
-#pragma unroll
-    for (int rb = 0; rb < NR; ++rb) {
-        const int g = g0 + 16 * rb + x;
-        const bool valid = g < G;
-        const int64_t row = (int64_t)b * Hq + h * G + (valid ? g : 0);
-        orow[rb] = !valid ? -1 : ns > 1 ? row * ns + sp : row * (k + 1) + k;
-        load_q<MOSKA_BF16>(qf[rb], a.Q, row * HD, valid, q);
-    }
     const int len = a.unique_len ? min(max(a.unique_len[b], 0), U) : U;
     const int per = ((len + ns - 1) / ns + 31) & ~31;       // keys per slice, whole 32-key tiles
     const int k0 = min(sp * per, len), nkeys = min(per, len - k0);
+    uint32_t qf[NR][4][4];
+    int64_t orow[NR];
+    int lim[NR];                                            // keys of this slice the lane's rows may see
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) {
+        const int r = r0 + 16 * rb + x;
+        const bool valid = r < R;
+        const int t = valid ? r / G : T - 1, g = valid ? r - t * G : 0;
+        const int64_t row = ((int64_t)b * T + t) * Hq + h * G + g;
+        orow[rb] = !valid ? -1 : ns > 1 ? row * ns + sp : row * (k + 1) + k;
+        lim[rb] = min(max(len - (T - 1 - t) - k0, 0), nkeys);
+        load_q<MOSKA_BF16>(qf[rb], a.Q, row * HD, valid, q);
+    }
+    // the workgroup's earliest token bounds what every row sees
+    const int t_first = min(r0 / G, T - 1);
+    const int nsafe = min(max(len - (T - 1 - t_first) - k0, 0), nkeys);
     const int64_t base = (((int64_t)b * Hkv + h) * U + k0) * row_bytes<MOSKA_BF16>();
     WaveState<NR> st;
-    attend<NR, MOSKA_BF16, NW, AUX, NKB>(st, qf, (const char *)a.Ku + base, (const char *)a.Vu + base, nkeys,
+    attend<NR, MOSKA_BF16, NW, AUX, NKB>(st, qf, (const char *)a.Ku + base, (const char *)a.Vu + base, nkeys, nsafe, lim,
                                          scale * kLog2e, wave, q, x);
     combine_and_store<NR, NW>(st, comb, wave, q, x, orow, 1.f, ns > 1 ? a.split_O : a.part_O,
                               ns > 1 ? a.split_LSE : a.part_LSE);

@@ -76,8 +76,9 @@ int launch_unique_mfma(const moska_problem_t &p, const UniqueArgs &a, hipStream_
         MOSKA_UV(1, 4, 2, 1), MOSKA_UV(1, 4, 2, 2), MOSKA_UV(1, 8, 2, 1), MOSKA_UV(2, 4, 2, 1), MOSKA_UV(4, 4, 2, 2),
     };
 #undef MOSKA_UV
-    const int G = p.Hq / p.Hkv;
-    const int NR = G <= 16 ? 1 : G <= 32 ? 2 : 4;
+    int T = q_len(p);
+    const int R = T * (p.Hq / p.Hkv);                          // query rows per (request, KV head)
+    const int NR = R <= 16 ? 1 : R <= 32 ? 2 : 4;
     int want = 0;
     if (const char *e = std::getenv("MOSKA_UNIQUE_VARIANT")) want = std::atoi(e);
     const UniqueVariant *pick = nullptr;
@@ -87,15 +88,15 @@ int launch_unique_mfma(const moska_problem_t &p, const UniqueArgs &a, hipStream_
             if (!pick || seen == want) pick = &uv;
             ++seen;
         }
-    const int gt = (G + 16 * NR - 1) / (16 * NR);
+    const int gt = (R + 16 * NR - 1) / (16 * NR);
     const unsigned grid = (unsigned)((int64_t)p.B * p.Hkv * gt * a.nsplit);
     UniqueArgs args = a;
     int Hq = p.Hq, Hkv = p.Hkv, U = p.U_max, k = p.k;
     float scale = p.scale;
-    void *kargs[] = {&args, &Hq, &Hkv, &U, &k, &scale};
+    void *kargs[] = {&args, &Hq, &Hkv, &U, &k, &scale, &T};
     if (hipLaunchKernel(pick->kernel, dim3(grid), dim3(pick->v.NW * 64), kargs, 0, s) != hipSuccess) return MOSKA_ERR_HIP;
     if (a.nsplit > 1)
-        return launch_split_combine(a.split_O, a.split_LSE, a.nsplit, (int64_t)p.B * p.Hq, p.k, 1, p.k, a.part_O,
+        return launch_split_combine(a.split_O, a.split_LSE, a.nsplit, (int64_t)p.B * T * p.Hq, p.k, 1, p.k, a.part_O,
                                     a.part_LSE, s);
     return MOSKA_OK;
 }

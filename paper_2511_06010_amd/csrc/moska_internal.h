@@ -97,6 +97,17 @@ int launch_merge(const moska_problem_t &p, const float *part_O, const float *par
 int launch_chunk_embeddings(const moska_problem_t &p, const void *Ks, const float *scale_k, void *E, hipStream_t s);
 int launch_quantize_fp8(const moska_problem_t &p, const void *X, void *X8, float *scale, hipStream_t s);
 
+// query tokens per request (0 in the descriptor reads as 1) and in the whole step
+inline int q_len(const moska_problem_t &p) { return p.q_len > 0 ? p.q_len : 1; }
+// The same step with every query token as a request of its own: what routing, bucketing, shared
+// attention and the merge work on (only unique attention needs to know which tokens share a context).
+inline moska_problem_t per_token(const moska_problem_t &p) {
+    moska_problem_t f = p;
+    f.B = p.B * q_len(p);
+    f.q_len = 1;
+    return f;
+}
+
 inline int hip_status(hipError_t e) { return e == hipSuccess ? MOSKA_OK : MOSKA_ERR_HIP; }
 
 // ---- storage dtype helpers (device) ----------------------------------------------------

@@ -43,6 +43,14 @@ SMALL = {
     "bf16-split-shared": P(B=12, Hq=8, Hkv=2, C=4, L=2500, k=2, U=40),
     "bf16-split-shared-hot": P(B=200, Hq=16, Hkv=2, C=2, L=1536, k=1, U=16),
     "fp8-split-shared": P(kv_dtype="fp8", B=40, Hq=16, Hkv=2, C=3, L=1100, k=2, U=30),
+    # several query tokens per request: token t sees the unique context up to its own position
+    "bf16-t3-ragged": P(T=3, B=7, Hq=8, Hkv=2, C=6, L=100, k=2, U=90),
+    "bf16-t8-g4": P(T=8, B=5, Hq=16, Hkv=4, C=6, L=96, k=2, U=200),                # 32 rows per (request, KV head)
+    "bf16-t5-g8-ragged": P(T=5, B=3, Hq=16, Hkv=2, C=5, L=64, k=2, U=150),         # 40 rows: the 64-row kernel
+    "bf16-t40": P(T=40, B=2, Hq=4, Hkv=2, C=5, L=64, k=2, U=130),                  # two row tiles, two masked key tiles
+    "bf16-t2-split-unique-ragged": P(T=2, B=2, Hq=8, Hkv=2, C=4, L=64, k=2, U=3000),
+    "fp8-t4": P(kv_dtype="fp8", T=4, B=6, Hq=16, Hkv=2, C=4, L=128, k=2, U=70),
+    "f32-t3-ragged": P(q_dtype="f32", kv_dtype="f32", T=3, B=4, Hq=6, Hkv=3, D=64, C=5, L=60, k=2, U=50),
     # head sizes 256 (widest matrix-core routing kernel) and 48 (vector-ALU routing kernel)
     "bf16-d256": P(D=256, B=19, Hq=8, Hkv=2, C=21, L=70, k=3, U=20),
     "f32-d256": P(q_dtype="f32", kv_dtype="f32", D=256, B=5, Hq=4, Hkv=2, C=18, L=40, k=2, U=10),
