@@ -227,7 +227,8 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    per_call_ms = {c: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps for i, c in enumerate(calls)}
+    samples = {c: sorted(e[i].elapsed_time(e[i + 1]) for e in evs) for i, c in enumerate(calls)}
+    per_call_ms = {c: sum(v) / len(v) for c, v in samples.items()}
 
     # the same step through the single entry point (it may overlap unique attention with the rest)
     def fused():
@@ -261,7 +262,8 @@ def main():
         ms = per_call_ms[c]
         gbs = work[c]["bytes"] / (ms * 1e-3) / 1e9
         tfl = work[c]["flops"] / (ms * 1e-3) / 1e12
-        kernels[c] = {"ms": round(ms, 5), "GB/s": round(gbs, 1), "TFLOP/s": round(tfl, 2),
+        kernels[c] = {"ms": round(ms, 5), "ms_median": round(samples[c][len(samples[c]) // 2], 5),
+                      "ms_min": round(samples[c][0], 5), "GB/s": round(gbs, 1), "TFLOP/s": round(tfl, 2),
                       "hbm_frac": round(gbs / HBM_PEAK_GBS, 4), "mfma_frac": round(tfl / MFMA_BF16_PEAK_TFLOPS, 4)}
     att_s = shared_attainable_s(p, buf.bucket_off.cpu())
     kernels["shared_attn"]["roofline_ms"] = round(att_s * 1e3, 5)          # sum over buckets of max(HBM, MFMA) time

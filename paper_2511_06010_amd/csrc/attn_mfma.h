@@ -595,9 +595,5 @@ __global__ __launch_bounds__(NW * 64, min_waves(NR)) void unique_mfma_kernel(Uni
                               ns > 1 ? a.split_LSE : a.part_LSE);
 }
 
-// Tuning variant of a kernel instantiation: row blocks, waves per workgroup, load cache policy,
-// key tiles in flight.
-struct Variant { int NR, NW, AUX, NKB; };
-
 }  // namespace mfma
 }  // namespace moska

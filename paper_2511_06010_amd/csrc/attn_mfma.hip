@@ -65,36 +65,21 @@ int launch_shared_mfma(const moska_problem_t &p, const SharedArgs &a, const Shar
 
 int launch_unique_mfma(const moska_problem_t &p, const UniqueArgs &a, hipStream_t s) {
     using namespace mfma;
-    struct UniqueVariant {
-        Variant v;
-        const void *kernel;
-    };
-#define MOSKA_UV(NR, NW, AUX, NKB) \
-    UniqueVariant { Variant{NR, NW, AUX, NKB}, (const void *)unique_mfma_kernel<NR, NW, AUX, NKB> }
-    // first entry of each row count is the default; MOSKA_UNIQUE_VARIANT=<index> picks another
-    static const UniqueVariant table[] = {
-        MOSKA_UV(1, 4, 2, 1), MOSKA_UV(1, 4, 2, 2), MOSKA_UV(1, 8, 2, 1), MOSKA_UV(2, 4, 2, 1), MOSKA_UV(4, 4, 2, 2),
-    };
-#undef MOSKA_UV
+    // 16, 32 or 64 query rows per workgroup; 4 waves split the keys, non-temporal loads, one key tile
+    // in flight per wave (two for the 64-row kernel, which runs one wave per SIMD)
     int T = q_len(p);
     const int R = T * (p.Hq / p.Hkv);                          // query rows per (request, KV head)
     const int NR = R <= 16 ? 1 : R <= 32 ? 2 : 4;
-    int want = 0;
-    if (const char *e = std::getenv("MOSKA_UNIQUE_VARIANT")) want = std::atoi(e);
-    const UniqueVariant *pick = nullptr;
-    int seen = 0;
-    for (const UniqueVariant &uv : table)
-        if (uv.v.NR == NR) {
-            if (!pick || seen == want) pick = &uv;
-            ++seen;
-        }
+    const void *kernel = NR == 1 ? (const void *)unique_mfma_kernel<1, 4, 2, 1>
+                         : NR == 2 ? (const void *)unique_mfma_kernel<2, 4, 2, 1>
+                                   : (const void *)unique_mfma_kernel<4, 4, 2, 2>;
     const int gt = (R + 16 * NR - 1) / (16 * NR);
     const unsigned grid = (unsigned)((int64_t)p.B * p.Hkv * gt * a.nsplit);
     UniqueArgs args = a;
     int Hq = p.Hq, Hkv = p.Hkv, U = p.U_max, k = p.k;
     float scale = p.scale;
     void *kargs[] = {&args, &Hq, &Hkv, &U, &k, &scale, &T};
-    if (hipLaunchKernel(pick->kernel, dim3(grid), dim3(pick->v.NW * 64), kargs, 0, s) != hipSuccess) return MOSKA_ERR_HIP;
+    if (hipLaunchKernel(kernel, dim3(grid), dim3(256), kargs, 0, s) != hipSuccess) return MOSKA_ERR_HIP;
     if (a.nsplit > 1)
         return launch_split_combine(a.split_O, a.split_LSE, a.nsplit, (int64_t)p.B * T * p.Hq, p.k, 1, p.k, a.part_O,
                                     a.part_LSE, s);

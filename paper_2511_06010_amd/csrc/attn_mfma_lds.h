@@ -253,7 +253,7 @@ __global__ __launch_bounds__(NWV * 64, lds_min_waves(NR)) void shared_lds_kernel
 // from its end: the largest tiles start first.
 constexpr int MIXED_KT = 64;       // keys per LDS stage of the mixed launch (64 KiB of stages per workgroup)
 
-template <int KVD, int AUX, int PD1>
+template <int KVD, int AUX>
 __global__ __launch_bounds__(256, 2) void shared_mixed_kernel(SharedArgs a, int c0, int c1, int Hq, int Hkv, int C,
                                                                int L, int k, float scale) {
     __shared__ uint4 smem[lds_units<MIXED_KT>()];           // K/V stages, or the 33 KiB merge buffer
@@ -269,20 +269,8 @@ __global__ __launch_bounds__(256, 2) void shared_mixed_kernel(SharedArgs a, int 
     // flight of an fp8 LDS stage); a bf16 store is faster through LDS like the 64-row tiles.
     if (KVD == MOSKA_FP8_E4M3 && cls == 0) stream_tile<1, KVD, 4, AUX, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
     else if (KVD == MOSKA_FP8_E4M3 && cls == 1) stream_tile<2, KVD, 4, AUX, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
-    else if (cls <= 2) lds_tile<1, 4, KVD, AUX, MIXED_KT, PD1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
+    else if (cls <= 2) lds_tile<1, 4, KVD, AUX, MIXED_KT, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
     else lds_tile<2, 4, KVD, AUX, MIXED_KT, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
-}
-
-// Classes [c0, c1] of at most 64 rows, every tile on the LDS-staged path with 16 rows per wave.
-template <int KVD, int AUX, int KT, int PD, int MINW>
-__global__ __launch_bounds__(256, MINW) void shared_small_kernel(SharedArgs a, int c0, int c1, int Hq, int Hkv, int C,
-                                                                  int L, int k, float scale) {
-    __shared__ uint4 smem[lds_units<KT>()];
-    const int first = a.tile_hdr[c0], end = a.tile_hdr[c1 + 1];
-    const int w = xcd_tile_index(end - first);
-    if (w < 0) return;
-    const int t = end - 1 - w;
-    lds_tile<1, 4, KVD, AUX, KT, PD>(a, a.tiles[2 * t], a.tiles[2 * t + 1], Hq, Hkv, C, L, k, scale, smem);
 }
 
 }  // namespace mfma

@@ -244,6 +244,9 @@ def test_invalid_arguments_are_rejected_before_launch():
         moska.route(p, inp.Q, inp.E, buf.ids, None, buf.ws[:16])
     with pytest.raises(moska.MoskaError, match="unsupported"):
         moska.workspace_bytes(p.with_(D=72))
+    with pytest.raises(moska.MoskaError, match="invalid"):
+        moska.workspace_bytes(p.with_(T=-1))
+    assert moska.workspace_bytes(p.with_(T=0)) == moska.workspace_bytes(p)       # q_len 0 reads as 1
     with pytest.raises(moska.MoskaError, match="workspace"):
         moska.bucket(p, buf.ids, buf.bucket_off, buf.bucket_items, buf.ws[:16])
     with pytest.raises(moska.MoskaError, match="invalid"):       # fp8 store without scales
