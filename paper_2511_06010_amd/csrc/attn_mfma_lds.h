@@ -1,9 +1,10 @@
-// Shared KV Attention for large buckets (64, 128 or 256 query rows per tile), paper Sec. III-A:
-// the regime where batching the queries of a chunk turns the chunk's K/V stream into a GEMM.
+// Shared KV Attention on LDS-staged tiles of 64, 128 or 256 query rows (smaller row counts pad a
+// 64-row tile), paper Sec. III-A: the regime where batching the queries of a chunk turns the chunk's
+// K/V stream into a GEMM.
 //
 // A workgroup of NWV waves owns 16*NR*NWV rows of one bucket; each wave owns 16*NR of them for
 // ALL keys of the chunk, so no cross-wave merge is needed.  The chunk's K and V are streamed
-// from HBM once per workgroup: every thread fetches a slice of the next 32-key stage into
+// from HBM once per workgroup: every thread fetches a slice of the next KT-key stage into
 // registers while the current stage is consumed from LDS, then writes its slice to the other
 // LDS buffer (an fp8 store is widened to bf16 here, once per workgroup instead of once per
 // wave).  One barrier per stage.
@@ -125,14 +126,12 @@ __device__ __forceinline__ void pv_from_lds(WaveState<NR> &st, const uint4 *lv, 
 template <int KT> constexpr int lds_units() { return 4 * KT * 16; }
 
 // Tile (bkt, row0) on the LDS-staged path: 16*NR*NWV rows.  smem: lds_units<KT>() uint4.
-// KT keys per stage (32 or 64); PD stages of global loads are kept in flight in registers (2 or 4):
+// KT keys per stage (32 or 64); PD stages of global loads are kept in flight in registers (1, 2 or 4):
 // the loads of stage t+1+PD are issued when stage t+1 has been copied to LDS, so they have PD
 // stages of MFMA work to land.
 template <int NR, int NWV, int KVD, int AUX, int KT, int PD>
-__device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0, int Hq, int Hkv, int C, int L, int k,
-                                         float scale, uint4 *smem) {
-    int bkt_key0 = 0;                                      // first key of this workgroup's slice
-    const int Lfull = L;
+__device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0, int Hq, int Hkv, int C, int Lchunk,
+                                         int k, float scale, uint4 *smem) {
     static_assert(KT == 32 || KT == 64, "keys per stage");
     static_assert(PD == 1 || PD == 2 || PD == 4, "stages in flight");
     constexpr int T = NWV * 64;
@@ -160,16 +159,13 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
         }
         load_q<MOSKA_BF16>(qf[rb], a.Q, qoff, valid, q);    // keys sit in LDS as bf16 in natural dim order
     }
-    {   // this workgroup's slice of the chunk (all of it unless the chunks are split over workgroups)
-        int k0, nk;
-        key_slice(L, a.nsplit, blockIdx.y, KT, k0, nk);
-        L = nk;
-        bkt_key0 = k0;
-    }
+    // this workgroup's keys: L of them from first_key on (the whole chunk unless chunks are split over workgroups)
+    int first_key, L;
+    key_slice(Lchunk, a.nsplit, blockIdx.y, KT, first_key, L);
     const float kmul = a.scale_k ? a.scale_k[c * Hkv + h] : 1.f;
     const float vmul = a.scale_v ? a.scale_v[c * Hkv + h] : 1.f;
     const float sc = scale * kmul * kLog2e;
-    const int64_t base = (((int64_t)c * Hkv + h) * Lfull + bkt_key0) * row_bytes<KVD>();
+    const int64_t base = (((int64_t)c * Hkv + h) * Lchunk + first_key) * row_bytes<KVD>();
     const __amdgpu_buffer_rsrc_t rk = key_set_rsrc((const char *)a.Ks + base, (uint32_t)L * row_bytes<KVD>());
     const __amdgpu_buffer_rsrc_t rv = key_set_rsrc((const char *)a.Vs + base, (uint32_t)L * row_bytes<KVD>());
 
