@@ -123,12 +123,15 @@ def check_against_oracle(inp_cpu: Inputs, label: str = ""):
 
 
 def sub_inputs(inp: Inputs, ids: torch.Tensor, b: int, h: int) -> tuple[Inputs, torch.Tensor]:
-    """The single-(request, KV head) problem of (b,h): its k routed chunks gathered into a compact
-    store, its G query heads and its unique context, as CPU tensors for the oracle."""
+    """The single-(query token, KV head) problem of (b,h): its k routed chunks gathered into a
+    compact store, its G query heads and the unique context it may see, as CPU tensors for the
+    oracle.  With several query tokens per request, b counts query tokens (request b // T, token
+    b % T) and the sub-problem is the single-token one with the context cut at the token."""
     p = inp.prob
     G = p.G
+    req, t = divmod(b, p.T)
     sel = ids[b, h].long().to(inp.Ks.device)
-    sp = p.with_(B=1, Hq=G, Hkv=1, C=p.k, name=p.name + f"-sub{b}.{h}")
+    sp = p.with_(B=1, T=1, Hq=G, Hkv=1, C=p.k, name=p.name + f"-sub{b}.{h}")
     cpu = lambda t: t.contiguous().cpu()
     sub = Inputs(
         sp,
@@ -138,10 +141,10 @@ def sub_inputs(inp: Inputs, ids: torch.Tensor, b: int, h: int) -> tuple[Inputs, 
         Vs=cpu(inp.Vs[sel, h:h + 1]),
         scale_k=None if inp.scale_k is None else cpu(inp.scale_k[sel, h:h + 1]),
         scale_v=None if inp.scale_v is None else cpu(inp.scale_v[sel, h:h + 1]),
-        Ku=cpu(inp.Ku[b:b + 1, h:h + 1]),
-        Vu=cpu(inp.Vu[b:b + 1, h:h + 1]),
-        unique_len=cpu(inp.unique_len[b:b + 1]),
-        cstar=cpu(inp.cstar[b:b + 1]),
+        Ku=cpu(inp.Ku[req:req + 1, h:h + 1]),
+        Vu=cpu(inp.Vu[req:req + 1, h:h + 1]),
+        unique_len=cpu((inp.unique_len[req:req + 1] - (p.T - 1 - t)).clamp_min(0)),
+        cstar=cpu(inp.cstar[req:req + 1]),
     )
     sub_ids = torch.arange(p.k, dtype=torch.int32).reshape(1, 1, p.k)
     return sub, sub_ids

@@ -259,12 +259,15 @@ def test_invalid_arguments_are_rejected_before_launch():
 
 # ---------------------------------------------------------------- full benchmark sizes
 
-def _full_size_check(cfg_idx: int, n_pairs: int):
-    """Routing and bucketing verified for every item; attention on sampled (request, KV head)
-    pairs (all G heads, all k+1 partials, merged output) that the oracle computes one by one."""
+def _full_size_check(cfg_idx: int, n_pairs: int, q_len: int = 1):
+    """Routing and bucketing verified for every item; attention on sampled (query token, KV head)
+    pairs (all G heads, all k+1 partials, merged output) that the oracle computes one by one.
+    q_len > 1: the same number of query tokens from B / q_len requests."""
     p = config(cfg_idx)
+    if q_len > 1:
+        p = p.with_(T=q_len, B=p.B // q_len, name=p.name + f"-qlen{q_len}")
     print(f"full-size config {cfg_idx}: {p}", flush=True)
-    inp = generate(p, seed=20251106 + cfg_idx, device="cuda")
+    inp = generate(p, seed=20251106 + cfg_idx, device="cuda", unique_len="ragged" if q_len > 1 else "full")
     o_ids, _, o_all = oracle.route(p, inp.Q.cpu(), inp.E.cpu(), want_all_scores=True)
     buf = gpu_pipeline(inp)
     excused = check_route(p, buf.routed_ids, o_ids, o_all)
@@ -285,7 +288,9 @@ def _full_size_check(cfg_idx: int, n_pairs: int):
         item = int(items[off[bk + 1] - 1])
         pairs.add((item // p.k, h))
     while len(pairs) < n_pairs:
-        pairs.add((int(torch.randint(0, p.B, (1,), generator=g)), int(torch.randint(0, p.Hkv, (1,), generator=g))))
+        pairs.add((int(torch.randint(0, p.Bq, (1,), generator=g)), int(torch.randint(0, p.Hkv, (1,), generator=g))))
+    if q_len > 1:                 # the first and the last token of the requests with an empty and a full context
+        pairs.update({(0, 0), (q_len - 1, 0), (q_len, 1), (2 * q_len - 1, 1)})
     key = tol_key(p)
     G = p.G
     for b, h in sorted(pairs):
@@ -298,7 +303,8 @@ def _full_size_check(cfg_idx: int, n_pairs: int):
         assert_lse_close(buf.LSE[b, rows], st.LSE_direct[0], key, f"cfg{cfg_idx} LSE ({b},{h})")
     # properties that hold at any size: every slot written, outputs finite, LSE of the merge
     # above every partial LSE
-    assert torch.isfinite(buf.part_O).all() and torch.isfinite(buf.part_LSE).all()
+    assert torch.isfinite(buf.part_O).all() and torch.isfinite(buf.part_LSE[..., :p.k]).all()
+    assert not torch.isnan(buf.part_LSE).any()           # the unique slot is -inf where a token sees no unique key
     assert (buf.LSE[..., None] >= buf.part_LSE - 1e-3).all()
     print(f"  attention ok on {len(pairs)} sampled (request, head) pairs", flush=True)
     del inp, buf
@@ -313,3 +319,7 @@ def test_config1_full():
 @pytest.mark.parametrize("cfg_idx,n_pairs", [(2, 12), (3, 10), (4, 10)])
 def test_full_size_sampled(cfg_idx, n_pairs):
     _full_size_check(cfg_idx, n_pairs)
+
+
+def test_full_size_sampled_four_tokens_per_request():
+    _full_size_check(2, 12, q_len=4)
