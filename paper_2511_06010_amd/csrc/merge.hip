@@ -22,16 +22,29 @@ __global__ __launch_bounds__(256) void merge_kernel(const float *__restrict__ pa
     float wsum = 0.f;
     float4 acc = {0.f, 0.f, 0.f, 0.f};
     if (m != -INFINITY) {
-        for (int j = 0; j < P; ++j) {
-            const float lj = lse[j];
-            if (lj == -INFINITY) continue;             // an empty slot's O is never read
-            const float w = expf(lj - m);
-            wsum += w;
-            const float4 o = *(const float4 *)(part_O + (r * P + j) * D + 4 * t);
-            acc.x = fmaf(w, o.x, acc.x);
-            acc.y = fmaf(w, o.y, acc.y);
-            acc.z = fmaf(w, o.z, acc.z);
-            acc.w = fmaf(w, o.w, acc.w);
+        // four slots per round, their loads issued together; an empty slot's O may hold anything:
+        // it is loaded (the address is valid) but never enters the arithmetic
+        const float *po = part_O + r * P * D + 4 * t;
+        for (int j0 = 0; j0 < P; j0 += 4) {
+            float4 o[4];
+            float w[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = min(j0 + u, P - 1);
+                o[u] = *(const float4 *)(po + (int64_t)j * D);
+                const float lj = lse[j];
+                w[u] = (j0 + u < P && lj != -INFINITY) ? expf(lj - m) : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (w[u] != 0.f) {
+                    wsum += w[u];
+                    acc.x = fmaf(w[u], o[u].x, acc.x);
+                    acc.y = fmaf(w[u], o[u].y, acc.y);
+                    acc.z = fmaf(w[u], o[u].z, acc.z);
+                    acc.w = fmaf(w[u], o[u].w, acc.w);
+                }
+            }
         }
     }
     const float inv = wsum > 0.f ? 1.f / wsum : 0.f;
