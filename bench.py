@@ -256,6 +256,31 @@ def main():
     torch.cuda.synchronize()
     graph_ms = (time.perf_counter() - g0) * 1e3 / args.steps
 
+    # the five calls again with unique attention on a second stream (same priority), joined before the merge
+    side = torch.cuda.Stream()
+    fork, join = torch.cuda.Event(), torch.cuda.Event()
+
+    def two_streams():
+        fork.record()
+        with torch.cuda.stream(side):
+            side.wait_event(fork)
+            moska.unique_attn(p, inp.Q, inp.Ku, inp.Vu, inp.unique_len, buf.part_O, buf.part_LSE, buf.ws)
+            join.record()
+        moska.route(p, inp.Q, inp.E, buf.ids, None, buf.ws)
+        moska.bucket(p, buf.ids, buf.bucket_off, buf.bucket_items, buf.ws)
+        moska.shared_attn(p, inp.Q, inp.Ks, inp.Vs, inp.scale_k, inp.scale_v, buf.ids, buf.bucket_off,
+                          buf.bucket_items, buf.part_O, buf.part_LSE, buf.ws)
+        torch.cuda.current_stream().wait_event(join)
+        moska.merge(p, buf.part_O, buf.part_LSE, buf.O, buf.LSE)
+    for _ in range(args.warmup):
+        two_streams()
+    torch.cuda.synchronize()
+    s0 = time.perf_counter()
+    for _ in range(args.steps):
+        two_streams()
+    torch.cuda.synchronize()
+    two_stream_ms = (time.perf_counter() - s0) * 1e3 / args.steps
+
     work = algorithmic_work(p, buf.bucket_off.cpu())
     kernels = {}
     for c in calls:
@@ -290,6 +315,7 @@ def main():
         "kernels": kernels,
         "decode_step_ms": round(decode_step_ms, 5),
         "decode_step_graph_ms": round(graph_ms, 5),
+        "two_stream_ms": round(two_stream_ms, 5),
         "roofline": roofline,
     }
 

@@ -382,6 +382,13 @@ __device__ __forceinline__ void attend(WaveState<NR> &st, const uint32_t (&qf)[N
     }
 }
 
+// The LDS-staged tiles write their partial rows (64-byte pieces, a whole row within a few
+// instructions) with the non-temporal hint.  Mixed into a saturated K/V read stream, plain write-back
+// stores of these rows cost far more than their bytes (measured at 256 requests x 8 chunks: 34 MB of
+// partials stretch a 0.61 ms stream to 0.71 ms, to 0.65 ms with the hint).  The 16-byte pieces of the
+// streaming layout and the 4-byte LSE values stay write-back, so that the L2 can assemble lines.
+__device__ __forceinline__ void store_partial16(float *p, const f32x4 &v) { __builtin_nontemporal_store(v, (f32x4 *)p); }
+
 // Normalise and write the rows a wave holds (st.l already summed over the row's four lanes).
 // orow[rb]: index of row 16rb+x in part_LSE (part_O row = orow*HD), or -1 for a padding row.
 // DIMS16 = false: component r of o[rb][e] is dim 32q + 8r + e (operands transposed in registers);
@@ -398,8 +405,8 @@ __device__ __forceinline__ void store_rows(const WaveState<NR> &st, int q, const
             float *o = part_O + orow[rb] * HD + 4 * q;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float4 v = {st.o[rb][e][0] * inv, st.o[rb][e][1] * inv, st.o[rb][e][2] * inv, st.o[rb][e][3] * inv};
-                *(float4 *)(o + 16 * e) = v;
+                const f32x4 v = {st.o[rb][e][0] * inv, st.o[rb][e][1] * inv, st.o[rb][e][2] * inv, st.o[rb][e][3] * inv};
+                store_partial16(o + 16 * e, v);
             }
         } else {
             float *o = part_O + orow[rb] * HD + 32 * q;

@@ -138,10 +138,22 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
     constexpr int SU = KT * 16;                            // uint4 units of K (or V) per stage
     uint4 *ldsK = smem, *ldsV = smem + 2 * SU;
     const int h = bkt / C, c = bkt - h * C, G = Hq / Hkv;
-    const int beg = a.off[bkt], rows = (a.off[bkt + 1] - beg) * G;
     const int tid = threadIdx.x, lane = tid & 63, q = lane >> 4, x = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
+    // this workgroup's keys: L of them from first_key on (the whole chunk unless chunks are split over
+    // workgroups).  Their first stage is requested before anything else: the bucket -> item -> query row
+    // chain below is three dependent loads, a long time to have nothing else in flight.
+    int first_key, L;
+    key_slice(Lchunk, a.nsplit, blockIdx.y, KT, first_key, L);
+    const int64_t base = (((int64_t)c * Hkv + h) * Lchunk + first_key) * row_bytes<KVD>();
+    const __amdgpu_buffer_rsrc_t rk = key_set_rsrc((const char *)a.Ks + base, (uint32_t)L * row_bytes<KVD>());
+    const __amdgpu_buffer_rsrc_t rv = key_set_rsrc((const char *)a.Vs + base, (uint32_t)L * row_bytes<KVD>());
+    const int nst = (L + KT - 1) / KT;                     // stages; rows past L read as zeros
+    StageRegs<KVD, T, KT> regs[PD];                        // PD >= 2: regs[(t+1+j) % PD] carries stage t+1+j at step t
+    stage_fetch<KVD, T, KT, AUX>(regs[0], rk, rv, 0, tid);
+
+    const int beg = a.off[bkt], rows = (a.off[bkt + 1] - beg) * G;
     uint32_t qf[NR][4][4];
     int64_t orow[NR];
 #pragma unroll
@@ -159,15 +171,9 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
         }
         load_q<MOSKA_BF16>(qf[rb], a.Q, qoff, valid, q);    // keys sit in LDS as bf16 in natural dim order
     }
-    // this workgroup's keys: L of them from first_key on (the whole chunk unless chunks are split over workgroups)
-    int first_key, L;
-    key_slice(Lchunk, a.nsplit, blockIdx.y, KT, first_key, L);
     const float kmul = a.scale_k ? a.scale_k[c * Hkv + h] : 1.f;
     const float vmul = a.scale_v ? a.scale_v[c * Hkv + h] : 1.f;
     const float sc = scale * kmul * kLog2e;
-    const int64_t base = (((int64_t)c * Hkv + h) * Lchunk + first_key) * row_bytes<KVD>();
-    const __amdgpu_buffer_rsrc_t rk = key_set_rsrc((const char *)a.Ks + base, (uint32_t)L * row_bytes<KVD>());
-    const __amdgpu_buffer_rsrc_t rv = key_set_rsrc((const char *)a.Vs + base, (uint32_t)L * row_bytes<KVD>());
 
     WaveState<NR> st;
 #pragma unroll
@@ -178,10 +184,11 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
         for (int e = 0; e < 8; ++e) st.o[rb][e] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    const int nst = (L + KT - 1) / KT;                     // stages; rows past L read as zeros
-    StageRegs<KVD, T, KT> regs[PD];                        // PD >= 2: regs[(t+1+j) % PD] carries stage t+1+j at step t
+    // a wave whose rows all lie past the bucket's end only helps to stage K and V
+    const bool has_rows = row0 + wave * (16 * NR) < rows;
     // stage t out of LDS buffer `cur`: scores, softmax, output for its 32-key sub-tiles
     auto consume = [&](int t, int cur) {
+        if (!has_rows) return;
 #pragma unroll
         for (int sub = 0; sub < KT / 32; ++sub) {
             f32x4 s[NR][2];
@@ -193,7 +200,6 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
             pv_from_lds<NR>(st, ldsV + cur * SU + sub * 512, pf, lane);
         }
     };
-    stage_fetch<KVD, T, KT, AUX>(regs[0], rk, rv, 0, tid);
     stage_store<KVD, T, KT>(regs[0], ldsK, ldsV, tid);
     if constexpr (PD == 1) {
         __syncthreads();
