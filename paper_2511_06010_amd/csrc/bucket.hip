@@ -121,44 +121,83 @@ __device__ __forceinline__ int tile_class(int rem, int cmin, int cmax) {
 }
 
 // Tile list grouped by size class: hdr[c] = first entry of class c, hdr[kNumClasses] = total;
-// entry t = (bucket, first row).  Inside a class the entries keep bucket order, so the tiles of
-// one bucket are neighbours.
+// entry t = (bucket, first row).  A bucket of r rows gives (r-1)/R full tiles of the largest class
+// in use (R rows) and one tile of the smallest class that holds the rest.  Thread t owns buckets
+// t, t+T, t+2T, ... (coalesced reads of the offsets); inside a class the entries are ordered by
+// owner thread, then bucket, so the tiles of one bucket are neighbours.
+constexpr int kTileListLds = 15360;     // bucket row counts kept in LDS up to this many buckets
+
 __global__ __launch_bounds__(1024) void tile_list_kernel(const int32_t *__restrict__ off, int NB, int G, int cmin,
                                                           int cmax, int32_t *__restrict__ hdr,
                                                           int32_t *__restrict__ tiles) {
-    __shared__ int tmp[1024];
+    __shared__ int tmp[16 * kNumClasses];
     __shared__ int cstart[kNumClasses + 1];
-    const int per = (NB + blockDim.x - 1) / blockDim.x;
-    const int b0 = threadIdx.x * per, b1 = min(NB, b0 + per);
-    int mine[kNumClasses] = {0, 0, 0, 0, 0};
-    for (int b = b0; b < b1; ++b) {
-        int rem = (off[b + 1] - off[b]) * G;
-        while (rem > 0) {
-            const int c = tile_class(rem, cmin, cmax);
-            mine[c] += 1;
-            rem -= class_rows(c);
-        }
-    }
-    int pre[kNumClasses];
-    if (threadIdx.x == 0) cstart[0] = 0;
-    for (int c = 0; c < kNumClasses; ++c) {
-        int total;
-        pre[c] = block_exclusive_scan(mine[c], tmp, &total);
-        if (threadIdx.x == 0) cstart[c + 1] = cstart[c] + total;
+    __shared__ int rows_lds[kTileListLds];
+    const int T = blockDim.x, tid = threadIdx.x;
+    const bool staged = NB <= kTileListLds;
+    if (staged) {
+        for (int b = tid; b < NB; b += T) rows_lds[b] = (off[b + 1] - off[b]) * G;
         __syncthreads();
     }
-    for (int b = b0; b < b1; ++b) {
-        int rem = (off[b + 1] - off[b]) * G, r0 = 0;
-        while (rem > 0) {
-            const int c = tile_class(rem, cmin, cmax);
-            const int pos = cstart[c] + pre[c]++;
-            tiles[2 * pos] = b;
-            tiles[2 * pos + 1] = r0;
-            r0 += class_rows(c);
-            rem -= class_rows(c);
-        }
+    auto rows_of = [&](int b) { return staged ? rows_lds[b] : (off[b + 1] - off[b]) * G; };
+    const int R = class_rows(cmax);
+    int mine[kNumClasses] = {0, 0, 0, 0, 0};
+    for (int b = tid; b < NB; b += T) {
+        const int r = rows_of(b);
+        if (r <= 0) continue;
+        const int nfull = (r - 1) / R, c = tile_class(r - nfull * R, cmin, cmax);
+#pragma unroll
+        for (int cc = 0; cc < kNumClasses; ++cc) mine[cc] += (cc == c) + (cc == cmax ? nfull : 0);
     }
-    if (threadIdx.x <= kNumClasses) hdr[threadIdx.x] = cstart[threadIdx.x];
+    // exclusive scan of the five counters over the block's threads in one go: wave-level shuffles,
+    // then the (at most 16) wave totals through LDS
+    int pre[kNumClasses];
+    const int lane = tid & 63, wave = tid >> 6, nw = T >> 6;
+#pragma unroll
+    for (int cc = 0; cc < kNumClasses; ++cc) {
+        int incl = mine[cc];
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl, d);
+            if (lane >= d) incl += up;
+        }
+        if (lane == 63) tmp[wave * kNumClasses + cc] = incl;
+        pre[cc] = incl - mine[cc];
+    }
+    __syncthreads();
+    int first = 0;                                          // first entry of the class
+#pragma unroll
+    for (int cc = 0; cc < kNumClasses; ++cc) {
+        int before = 0, total = 0;
+        for (int w = 0; w < nw; ++w) {
+            const int t = tmp[w * kNumClasses + cc];
+            if (w < wave) before += t;
+            total += t;
+        }
+        pre[cc] += first + before;
+        if (tid == 0) cstart[cc] = first;
+        first += total;
+    }
+    if (tid == 0) cstart[kNumClasses] = first;
+    for (int b = tid; b < NB; b += T) {
+        const int r = rows_of(b);
+        if (r <= 0) continue;
+        const int nfull = (r - 1) / R, c = tile_class(r - nfull * R, cmin, cmax);
+        int pfull = 0, prem = 0;
+#pragma unroll
+        for (int cc = 0; cc < kNumClasses; ++cc) {
+            if (cc == cmax) { pfull = pre[cc]; pre[cc] += nfull; }
+            if (cc == c) prem = pre[cc]++;
+        }
+        for (int i = 0; i < nfull; ++i) {
+            tiles[2 * (pfull + i)] = b;
+            tiles[2 * (pfull + i) + 1] = i * R;
+        }
+        tiles[2 * prem] = b;
+        tiles[2 * prem + 1] = nfull * R;
+    }
+    __syncthreads();
+    if (tid <= kNumClasses) hdr[tid] = cstart[tid];
 }
 
 }  // namespace
