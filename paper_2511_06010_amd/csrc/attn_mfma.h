@@ -382,18 +382,17 @@ __device__ __forceinline__ void attend(WaveState<NR> &st, const uint32_t (&qf)[N
     }
 }
 
-// The LDS-staged tiles write their partial rows (64-byte pieces, a whole row within a few
-// instructions) with the non-temporal hint.  Mixed into a saturated K/V read stream, plain write-back
-// stores of these rows cost far more than their bytes (measured at 256 requests x 8 chunks: 34 MB of
-// partials stretch a 0.61 ms stream to 0.71 ms, to 0.65 ms with the hint).  The 16-byte pieces of the
-// streaming layout and the 4-byte LSE values stay write-back, so that the L2 can assemble lines.
+// Partial rows are written in pieces of at least 64 contiguous bytes with the non-temporal hint.
+// Mixed into a saturated K/V read stream, plain write-back stores of these rows cost far more than
+// their bytes (measured at 256 requests x 8 chunks: 34 MB of partials stretch a 0.61 ms stream to
+// 0.71 ms, to 0.65 ms with the hint).  The 4-byte LSE values stay write-back, so that the L2 can
+// assemble lines.
 __device__ __forceinline__ void store_partial16(float *p, const f32x4 &v) { __builtin_nontemporal_store(v, (f32x4 *)p); }
 
-// Normalise and write the rows a wave holds (st.l already summed over the row's four lanes).
-// orow[rb]: index of row 16rb+x in part_LSE (part_O row = orow*HD), or -1 for a padding row.
-// DIMS16 = false: component r of o[rb][e] is dim 32q + 8r + e (operands transposed in registers);
-// DIMS16 = true:  it is dim 16e + 4q + r (operands from the LDS transpose read).
-template <int NR, bool DIMS16 = false>
+// Normalise and write the rows a wave of the LDS-staged kernels holds (st.l already summed over the
+// row's four lanes): component r of o[rb][e] is dim 16e + 4q + r (operands from the LDS transpose
+// read).  orow[rb]: index of row 16rb+x in part_LSE (part_O row = orow*HD), or -1 for a padding row.
+template <int NR>
 __device__ __forceinline__ void store_rows(const WaveState<NR> &st, int q, const int64_t (&orow)[NR], float vmul,
                                            float *part_O, float *part_LSE) {
 #pragma unroll
@@ -401,28 +400,18 @@ __device__ __forceinline__ void store_rows(const WaveState<NR> &st, int q, const
         if (orow[rb] < 0) continue;
         const float l = st.l[rb];
         const float inv = l > 0.f ? vmul / l : 0.f;
-        if constexpr (DIMS16) {
-            float *o = part_O + orow[rb] * HD + 4 * q;
+        float *o = part_O + orow[rb] * HD + 4 * q;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const f32x4 v = {st.o[rb][e][0] * inv, st.o[rb][e][1] * inv, st.o[rb][e][2] * inv, st.o[rb][e][3] * inv};
-                store_partial16(o + 16 * e, v);
-            }
-        } else {
-            float *o = part_O + orow[rb] * HD + 32 * q;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float4 lo = {st.o[rb][0][r] * inv, st.o[rb][1][r] * inv, st.o[rb][2][r] * inv, st.o[rb][3][r] * inv};
-                const float4 hi = {st.o[rb][4][r] * inv, st.o[rb][5][r] * inv, st.o[rb][6][r] * inv, st.o[rb][7][r] * inv};
-                *(float4 *)(o + 8 * r) = lo;
-                *(float4 *)(o + 8 * r + 4) = hi;
-            }
+        for (int e = 0; e < 8; ++e) {
+            const f32x4 v = {st.o[rb][e][0] * inv, st.o[rb][e][1] * inv, st.o[rb][e][2] * inv, st.o[rb][e][3] * inv};
+            store_partial16(o + 16 * e, v);
         }
         if (q == 0) part_LSE[orow[rb]] = l > 0.f ? (st.m[rb] + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
     }
 }
 
-// Merge the NW waves' states pairwise through LDS and let wave 0 write the rows.
+// Merge the NW waves' states pairwise through LDS and write the rows (all threads of the
+// workgroup must call this: it contains barriers).
 template <int NR, int NW>
 __device__ __forceinline__ void combine_and_store(WaveState<NR> &st, float *lds, int wave, int q, int x,
                                                   const int64_t (&orow)[NR], float vmul, float *part_O,
@@ -469,7 +458,32 @@ __device__ __forceinline__ void combine_and_store(WaveState<NR> &st, float *lds,
         }
         __syncthreads();
     }
-    if (wave == 0) store_rows<NR>(st, q, orow, vmul, part_O, part_LSE);
+    // Wave 0 holds the result.  Its normalised rows go through LDS once more so that they leave as
+    // whole 512-byte rows (two per store instruction, all waves storing) with the non-temporal hint.
+    if (wave == 0) {
+#pragma unroll
+        for (int rb = 0; rb < NR; ++rb) {
+            float *row = lds + (16 * rb + x) * OSTRIDE;
+            const float l = st.l[rb];
+            const float inv = l > 0.f ? vmul / l : 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) row[32 * q + 8 * r + e] = st.o[rb][e][r] * inv;
+            if (q == 0) {
+                *(int64_t *)(row + HD + 2) = orow[rb];
+                if (orow[rb] >= 0)
+                    part_LSE[orow[rb]] = l > 0.f ? (st.m[rb] + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
+            }
+        }
+    }
+    __syncthreads();
+    const int col = threadIdx.x & 31;
+    for (int rr = threadIdx.x >> 5; rr < R; rr += 2 * NW) {
+        const float *row = lds + rr * OSTRIDE;
+        const int64_t o = *(const int64_t *)(row + HD + 2);
+        if (o >= 0) store_partial16(part_O + o * HD + 4 * col, *(const f32x4 *)(row + 4 * col));
+    }
 }
 
 // Q^T operand of a row (element offset qoff into Q, or zeros for a padding row)

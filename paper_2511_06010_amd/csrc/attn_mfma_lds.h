@@ -232,7 +232,7 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
     for (int rb = 0; rb < NR; ++rb) {
         st.l[rb] = row_lanes_sum(st.l[rb]);
     }
-    store_rows<NR, true>(st, q, orow, vmul, a.nsplit > 1 ? a.split_O : a.part_O,
+    store_rows<NR>(st, q, orow, vmul, a.nsplit > 1 ? a.split_O : a.part_O,
                          a.nsplit > 1 ? a.split_LSE : a.part_LSE);
 }
 
