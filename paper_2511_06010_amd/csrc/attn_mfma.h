@@ -224,19 +224,27 @@ __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)
             moved[rb] = mx[rb] > st.m[rb] + kLazy;
             any_moved |= moved[rb];
         }
-        if (__any(any_moved)) {
+        const bool resc = __any(any_moved);
+        float alpha[NR];
+#pragma unroll
+        for (int rb = 0; rb < NR; ++rb) alpha[rb] = 1.f;
+        if (resc) {
 #pragma unroll
             for (int rb = 0; rb < NR; ++rb) {
                 const float mn = moved[rb] ? mx[rb] : st.m[rb];
-                float alpha = __builtin_amdgcn_exp2f(st.m[rb] - mn);          // exactly 1 for rows that stay
-                if (EMPTY_ROWS && !moved[rb]) alpha = 1.f;                    // (-inf) - (-inf)
+                alpha[rb] = __builtin_amdgcn_exp2f(st.m[rb] - mn);            // exactly 1 for rows that stay
+                if (EMPTY_ROWS && !moved[rb]) alpha[rb] = 1.f;                // (-inf) - (-inf)
                 st.m[rb] = mn;
-                st.l[rb] *= alpha;
+                st.l[rb] *= alpha[rb];
+            }
+        }
+        if (resc) {
+#pragma unroll
+            for (int rb = 0; rb < NR; ++rb)
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) st.o[rb][e][r] *= alpha;
-            }
+                    for (int r = 0; r < 4; ++r) st.o[rb][e][r] *= alpha[rb];
         }
 #pragma unroll
         for (int rb = 0; rb < NR; ++rb) {
