@@ -50,6 +50,12 @@ __device__ __forceinline__ f32x4 mfma16(const uint32_t (&a)[4], const uint32_t (
                                                    0, 0, 0);
 }
 
+// acc + lo + hi of a packed pair of bf16
+__device__ __forceinline__ float dot2_ones(uint32_t pair, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc,
+                                           false);
+}
+
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {   // round to nearest even
     const f32x2 v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
@@ -149,9 +155,9 @@ __device__ __forceinline__ f32x2 cvt2_fp8(uint32_t w, bool upper) {
 
 // four fp8 bytes of w -> two dwords of packed bf16 (exact)
 __device__ __forceinline__ void fp8x4_to_bf16x4(uint32_t w, uint32_t &d0, uint32_t &d1) {
-    const f32x2 a = cvt2_fp8(w, false), b = cvt2_fp8(w, true);
-    d0 = __builtin_amdgcn_perm(__float_as_uint(a[1]), __float_as_uint(a[0]), kSelHi);
-    d1 = __builtin_amdgcn_perm(__float_as_uint(b[1]), __float_as_uint(b[0]), kSelHi);
+    // v_cvt_scalef32_pk_bf16_fp8: two bytes -> two bf16 per instruction (scale 1)
+    d0 = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false));
+    d1 = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true));
 }
 
 __device__ __forceinline__ uint32_t word(const uint4 &v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
@@ -205,9 +211,11 @@ __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)
     // (a factor 2^kLazy in the probabilities, harmless in fp32 sums and in bf16's exponent range);
     // otherwise nothing is rescaled.  First tile: m = -inf, always moves.
     if constexpr (NR <= 2) {
-        // all row blocks' maxima first, then ONE wave-uniform branch around the rescale of all of them
+        // Every lane tests its own eight scores against the row's threshold; only if some lane of
+        // the wave is over it are the row maxima completed across lanes and the references moved: ONE
+        // wave-uniform branch, no cross-lane work on the usual path.
         float v[NR][8], mx[NR];
-        bool moved[NR], any_moved = false;
+        bool over = false;
 #pragma unroll
         for (int rb = 0; rb < NR; ++rb) {
 #pragma unroll
@@ -220,20 +228,20 @@ __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)
                 }
             const float *w = v[rb];
             mx[rb] = fmaxf(fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])), fmaxf(fmaxf(w[4], w[5]), fmaxf(w[6], w[7])));
-            mx[rb] = row_lanes_max(mx[rb]) * sc;
-            moved[rb] = mx[rb] > st.m[rb] + kLazy;
-            any_moved |= moved[rb];
+            over |= mx[rb] * sc > st.m[rb] + kLazy;
         }
-        const bool resc = __any(any_moved);
+        const bool resc = __any(over);
         float alpha[NR];
 #pragma unroll
         for (int rb = 0; rb < NR; ++rb) alpha[rb] = 1.f;
         if (resc) {
 #pragma unroll
             for (int rb = 0; rb < NR; ++rb) {
-                const float mn = moved[rb] ? mx[rb] : st.m[rb];
+                const float rmx = row_lanes_max(mx[rb]) * sc;
+                const bool moved = rmx > st.m[rb] + kLazy;
+                const float mn = moved ? rmx : st.m[rb];
                 alpha[rb] = __builtin_amdgcn_exp2f(st.m[rb] - mn);            // exactly 1 for rows that stay
-                if (EMPTY_ROWS && !moved[rb]) alpha[rb] = 1.f;                // (-inf) - (-inf)
+                if (EMPTY_ROWS && !moved) alpha[rb] = 1.f;                    // (-inf) - (-inf)
                 st.m[rb] = mn;
                 st.l[rb] *= alpha[rb];
             }
@@ -249,17 +257,16 @@ __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)
 #pragma unroll
         for (int rb = 0; rb < NR; ++rb) {
             const float mn = EMPTY_ROWS && st.m[rb] == -INFINITY ? 0.f : st.m[rb];   // no key yet: exp2(-inf) = 0 below
-            float sum = 0.f;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                v[rb][i] = __builtin_amdgcn_exp2f(fmaf(v[rb][i], sc, -mn));
-                sum += v[rb][i];
-            }
-            st.l[rb] += sum;
+            for (int i = 0; i < 8; ++i) v[rb][i] = __builtin_amdgcn_exp2f(fmaf(v[rb][i], sc, -mn));
             pf[rb][0] = pack_bf16(v[rb][0], v[rb][1]);
             pf[rb][1] = pack_bf16(v[rb][2], v[rb][3]);
             pf[rb][2] = pack_bf16(v[rb][4], v[rb][5]);
             pf[rb][3] = pack_bf16(v[rb][6], v[rb][7]);
+            // the row sum takes the probabilities as the P V product sees them (rounded to bf16), two per
+            // instruction: v_dot2c_f32_bf16 against a pair of ones
+#pragma unroll
+            for (int i = 0; i < 4; ++i) st.l[rb] = dot2_ones(pf[rb][i], st.l[rb]);
         }
     } else {
         // four row blocks: one at a time, to keep the live scores within the register file
