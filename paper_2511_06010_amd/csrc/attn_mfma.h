@@ -402,12 +402,18 @@ __device__ __forceinline__ void attend(WaveState<NR> &st, const uint32_t (&qf)[N
 // their bytes (measured at 256 requests x 8 chunks: 34 MB of partials stretch a 0.61 ms stream to
 // 0.71 ms, to 0.65 ms with the hint).  The 4-byte LSE values stay write-back, so that the L2 can
 // assemble lines.
-__device__ __forceinline__ void store_partial16(float *p, const f32x4 &v) { __builtin_nontemporal_store(v, (f32x4 *)p); }
+// NT = false for the slices of a split run: the combine kernel reads them back at once, so they stay
+// write-back.  (A compile-time choice: the compiler folds a run-time choice between two otherwise
+// identical stores into one plain store.)
+template <bool NT> __device__ __forceinline__ void store_partial16(float *p, const f32x4 &v) {
+    if constexpr (NT) __builtin_nontemporal_store(v, (f32x4 *)p);
+    else *(f32x4 *)p = v;
+}
 
 // Normalise and write the rows a wave of the LDS-staged kernels holds (st.l already summed over the
 // row's four lanes): component r of o[rb][e] is dim 16e + 4q + r (operands from the LDS transpose
 // read).  orow[rb]: index of row 16rb+x in part_LSE (part_O row = orow*HD), or -1 for a padding row.
-template <int NR>
+template <int NR, bool NT>
 __device__ __forceinline__ void store_rows(const WaveState<NR> &st, int q, const int64_t (&orow)[NR], float vmul,
                                            float *part_O, float *part_LSE) {
 #pragma unroll
@@ -419,7 +425,7 @@ __device__ __forceinline__ void store_rows(const WaveState<NR> &st, int q, const
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const f32x4 v = {st.o[rb][e][0] * inv, st.o[rb][e][1] * inv, st.o[rb][e][2] * inv, st.o[rb][e][3] * inv};
-            store_partial16(o + 16 * e, v);
+            store_partial16<NT>(o + 16 * e, v);
         }
         if (q == 0) part_LSE[orow[rb]] = l > 0.f ? (st.m[rb] + __builtin_amdgcn_logf(l)) * kLn2 : -INFINITY;
     }
@@ -427,7 +433,7 @@ __device__ __forceinline__ void store_rows(const WaveState<NR> &st, int q, const
 
 // Merge the NW waves' states pairwise through LDS and write the rows (all threads of the
 // workgroup must call this: it contains barriers).
-template <int NR, int NW>
+template <int NR, int NW, bool NT>
 __device__ __forceinline__ void combine_and_store(WaveState<NR> &st, float *lds, int wave, int q, int x,
                                                   const int64_t (&orow)[NR], float vmul, float *part_O,
                                                   float *part_LSE) {
@@ -497,7 +503,7 @@ __device__ __forceinline__ void combine_and_store(WaveState<NR> &st, float *lds,
     for (int rr = threadIdx.x >> 5; rr < R; rr += 2 * NW) {
         const float *row = lds + rr * OSTRIDE;
         const int64_t o = *(const int64_t *)(row + HD + 2);
-        if (o >= 0) store_partial16(part_O + o * HD + 4 * col, *(const f32x4 *)(row + 4 * col));
+        if (o >= 0) store_partial16<NT>(part_O + o * HD + 4 * col, *(const f32x4 *)(row + 4 * col));
     }
 }
 
@@ -528,7 +534,7 @@ __device__ __forceinline__ int64_t shared_out_row(const SharedArgs &a, int64_t b
 // Tile (bkt, row0) of Shared KV Attention on the streaming path: up to 16*NR gathered rows of
 // bucket bkt against (slice blockIdx.y of) its chunk.  comb: LDS for the cross-wave merge,
 // (NW/2)*16*NR*OSTRIDE floats.
-template <int NR, int KVD, int NW, int AUX, int NKB>
+template <int NR, int KVD, int NW, int AUX, int NKB, bool SPLIT>
 __device__ __forceinline__ void stream_tile(const SharedArgs &a, int bkt, int row0, int Hq, int Hkv, int C, int L,
                                             int k, float scale, float *comb) {
     const int h = bkt / C, c = bkt - h * C, G = Hq / Hkv;
@@ -561,8 +567,8 @@ __device__ __forceinline__ void stream_tile(const SharedArgs &a, int bkt, int ro
     WaveState<NR> st;
     attend<NR, KVD, NW, AUX, NKB>(st, qf, (const char *)a.Ks + base, (const char *)a.Vs + base, nk, nk, nk,
                                   scale * kmul * kLog2e, wave, q, x);
-    combine_and_store<NR, NW>(st, comb, wave, q, x, orow, vmul, a.nsplit > 1 ? a.split_O : a.part_O,
-                              a.nsplit > 1 ? a.split_LSE : a.part_LSE);
+    combine_and_store<NR, NW, !SPLIT>(st, comb, wave, q, x, orow, vmul, SPLIT ? a.split_O : a.part_O,
+                                      SPLIT ? a.split_LSE : a.part_LSE);
 }
 
 // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of the tile
@@ -579,14 +585,14 @@ __device__ __forceinline__ int xcd_tile_index(int ntiles) {
 constexpr int min_waves(int NR) { return NR == 1 ? 3 : NR == 2 ? 2 : 1; }
 
 // One size class of the tile list, streaming path.
-template <int NR, int KVD, int NW, int AUX, int NKB>
+template <int NR, int KVD, int NW, int AUX, int NKB, bool SPLIT>
 __global__ __launch_bounds__(NW * 64, min_waves(NR)) void shared_mfma_kernel(SharedArgs a, int cls, int Hq, int Hkv,
                                                                               int C, int L, int k, float scale) {
     __shared__ float comb[(NW / 2) * 16 * NR * OSTRIDE];
     const int first = a.tile_hdr[cls];
     const int w = xcd_tile_index(a.tile_hdr[cls + 1] - first);
     if (w < 0) return;
-    stream_tile<NR, KVD, NW, AUX, NKB>(a, a.tiles[2 * (first + w)], a.tiles[2 * (first + w) + 1], Hq, Hkv, C, L, k,
+    stream_tile<NR, KVD, NW, AUX, NKB, SPLIT>(a, a.tiles[2 * (first + w)], a.tiles[2 * (first + w) + 1], Hq, Hkv, C, L, k,
                                        scale, comb);
 }
 
@@ -594,7 +600,7 @@ __global__ __launch_bounds__(NW * 64, min_waves(NR)) void shared_mfma_kernel(Sha
 // head) pair -- row t*G + g is query token t, head g of the group -- over one of nsplit contiguous
 // slices of the request's context (nsplit = 1: all of it, the result goes straight to slot k;
 // otherwise to the split workspace, combined afterwards).  Token t sees the first len - (T-1-t) keys.
-template <int NR, int NW, int AUX, int NKB>
+template <int NR, int NW, int AUX, int NKB, bool SPLIT>
 __global__ __launch_bounds__(NW * 64, min_waves(NR)) void unique_mfma_kernel(UniqueArgs a, int Hq, int Hkv, int U, int k,
                                                                               float scale, int T) {
     __shared__ float comb[(NW / 2) * 16 * NR * OSTRIDE];
@@ -627,8 +633,8 @@ __global__ __launch_bounds__(NW * 64, min_waves(NR)) void unique_mfma_kernel(Uni
     WaveState<NR> st;
     attend<NR, MOSKA_BF16, NW, AUX, NKB>(st, qf, (const char *)a.Ku + base, (const char *)a.Vu + base, nkeys, nsafe, lim,
                                          scale * kLog2e, wave, q, x);
-    combine_and_store<NR, NW>(st, comb, wave, q, x, orow, 1.f, ns > 1 ? a.split_O : a.part_O,
-                              ns > 1 ? a.split_LSE : a.part_LSE);
+    combine_and_store<NR, NW, !SPLIT>(st, comb, wave, q, x, orow, 1.f, SPLIT ? a.split_O : a.part_O,
+                                      SPLIT ? a.split_LSE : a.part_LSE);
 }
 
 }  // namespace mfma

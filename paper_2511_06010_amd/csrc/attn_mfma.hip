@@ -70,9 +70,13 @@ int launch_unique_mfma(const moska_problem_t &p, const UniqueArgs &a, hipStream_
     int T = q_len(p);
     const int R = T * (p.Hq / p.Hkv);                          // query rows per (request, KV head)
     const int NR = R <= 16 ? 1 : R <= 32 ? 2 : 4;
-    const void *kernel = NR == 1 ? (const void *)unique_mfma_kernel<1, 4, 2, 1>
-                         : NR == 2 ? (const void *)unique_mfma_kernel<2, 4, 2, 1>
-                                   : (const void *)unique_mfma_kernel<4, 4, 2, 2>;
+    // [split run?][row blocks]: the slices of a split run are written write-back for the combine kernel
+    static const void *const table[2][3] = {
+        {(const void *)unique_mfma_kernel<1, 4, 2, 1, false>, (const void *)unique_mfma_kernel<2, 4, 2, 1, false>,
+         (const void *)unique_mfma_kernel<4, 4, 2, 2, false>},
+        {(const void *)unique_mfma_kernel<1, 4, 2, 1, true>, (const void *)unique_mfma_kernel<2, 4, 2, 1, true>,
+         (const void *)unique_mfma_kernel<4, 4, 2, 2, true>}};
+    const void *kernel = table[a.nsplit > 1][NR == 1 ? 0 : NR == 2 ? 1 : 2];
     const int gt = (R + 16 * NR - 1) / (16 * NR);
     const unsigned grid = (unsigned)((int64_t)p.B * p.Hkv * gt * a.nsplit);
     UniqueArgs args = a;

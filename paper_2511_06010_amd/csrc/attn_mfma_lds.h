@@ -129,7 +129,7 @@ template <int KT> constexpr int lds_units() { return 4 * KT * 16; }
 // KT keys per stage (32 or 64); PD stages of global loads are kept in flight in registers (1, 2 or 4):
 // the loads of stage t+1+PD are issued when stage t+1 has been copied to LDS, so they have PD
 // stages of MFMA work to land.
-template <int NR, int NWV, int KVD, int AUX, int KT, int PD>
+template <int NR, int NWV, int KVD, int AUX, int KT, int PD, bool SPLIT>
 __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0, int Hq, int Hkv, int C, int Lchunk,
                                          int k, float scale, uint4 *smem) {
     static_assert(KT == 32 || KT == 64, "keys per stage");
@@ -232,21 +232,20 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
     for (int rb = 0; rb < NR; ++rb) {
         st.l[rb] = row_lanes_sum(st.l[rb]);
     }
-    store_rows<NR>(st, q, orow, vmul, a.nsplit > 1 ? a.split_O : a.part_O,
-                         a.nsplit > 1 ? a.split_LSE : a.part_LSE);
+    store_rows<NR, !SPLIT>(st, q, orow, vmul, SPLIT ? a.split_O : a.part_O, SPLIT ? a.split_LSE : a.part_LSE);
 }
 
 constexpr int lds_min_waves(int NR) { return NR >= 4 ? 1 : 2; }
 
 // One size class of the tile list, LDS-staged path.
-template <int NR, int NWV, int KVD, int AUX, int KT, int PD>
+template <int NR, int NWV, int KVD, int AUX, int KT, int PD, bool SPLIT>
 __global__ __launch_bounds__(NWV * 64, lds_min_waves(NR)) void shared_lds_kernel(SharedArgs a, int cls, int Hq, int Hkv,
                                                                                   int C, int L, int k, float scale) {
     __shared__ uint4 smem[lds_units<KT>()];
     const int first = a.tile_hdr[cls];
     const int w = xcd_tile_index(a.tile_hdr[cls + 1] - first);
     if (w < 0) return;
-    lds_tile<NR, NWV, KVD, AUX, KT, PD>(a, a.tiles[2 * (first + w)], a.tiles[2 * (first + w) + 1], Hq, Hkv, C, L, k,
+    lds_tile<NR, NWV, KVD, AUX, KT, PD, SPLIT>(a, a.tiles[2 * (first + w)], a.tiles[2 * (first + w) + 1], Hq, Hkv, C, L, k,
                                         scale, smem);
 }
 
@@ -255,7 +254,7 @@ __global__ __launch_bounds__(NWV * 64, lds_min_waves(NR)) void shared_lds_kernel
 // from its end: the largest tiles start first.
 constexpr int MIXED_KT = 64;       // keys per LDS stage of the mixed launch (64 KiB of stages per workgroup)
 
-template <int KVD, int AUX>
+template <int KVD, int AUX, bool SPLIT>
 __global__ __launch_bounds__(256, 2) void shared_mixed_kernel(SharedArgs a, int c0, int c1, int Hq, int Hkv, int C,
                                                                int L, int k, float scale) {
     __shared__ uint4 smem[lds_units<MIXED_KT>()];           // K/V stages, or the 33 KiB merge buffer
@@ -269,10 +268,10 @@ __global__ __launch_bounds__(256, 2) void shared_mixed_kernel(SharedArgs a, int 
     while (cls < c1 && t >= a.tile_hdr[cls + 1]) ++cls;
     // Tiles of up to 32 rows: an fp8 store streams them (each wave its own keys, twice the bytes in
     // flight of an fp8 LDS stage); a bf16 store is faster through LDS like the 64-row tiles.
-    if (KVD == MOSKA_FP8_E4M3 && cls == 0) stream_tile<1, KVD, 4, AUX, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
-    else if (KVD == MOSKA_FP8_E4M3 && cls == 1) stream_tile<2, KVD, 4, AUX, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
-    else if (cls <= 2) lds_tile<1, 4, KVD, AUX, MIXED_KT, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
-    else lds_tile<2, 4, KVD, AUX, MIXED_KT, 1>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
+    if (KVD == MOSKA_FP8_E4M3 && cls == 0) stream_tile<1, KVD, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
+    else if (KVD == MOSKA_FP8_E4M3 && cls == 1) stream_tile<2, KVD, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
+    else if (cls <= 2) lds_tile<1, 4, KVD, AUX, MIXED_KT, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
+    else lds_tile<2, 4, KVD, AUX, MIXED_KT, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
 }
 
 }  // namespace mfma

@@ -20,13 +20,21 @@ struct SharedKernel {
 // every class on its own instead.
 template <int KVD>
 int launch_shared_classes(const moska_problem_t &p, const SharedArgs &a, const SharedPlan &pl, hipStream_t s) {
-    static const SharedKernel table[] = {
-        {0, 256, (const void *)shared_mfma_kernel<1, KVD, 4, 2, 1>},
-        {1, 256, (const void *)shared_mfma_kernel<2, KVD, 4, 2, 1>},
-        {2, 256, (const void *)shared_lds_kernel<1, 4, KVD, 2, MIXED_KT, 1>},   // as in the mixed launch
-        {3, 256, (const void *)shared_lds_kernel<2, 4, KVD, 2, MIXED_KT, 1>},
-        {4, 512, (const void *)shared_lds_kernel<2, 8, KVD, 2, 64, 2>},
+    // [split run?][class]: the slices of a split run are written for the combine kernel (write-back), whole
+    // results with the non-temporal hint
+    static const SharedKernel table[2][5] = {
+        {{0, 256, (const void *)shared_mfma_kernel<1, KVD, 4, 2, 1, false>},
+         {1, 256, (const void *)shared_mfma_kernel<2, KVD, 4, 2, 1, false>},
+         {2, 256, (const void *)shared_lds_kernel<1, 4, KVD, 2, MIXED_KT, 1, false>},   // as in the mixed launch
+         {3, 256, (const void *)shared_lds_kernel<2, 4, KVD, 2, MIXED_KT, 1, false>},
+         {4, 512, (const void *)shared_lds_kernel<2, 8, KVD, 2, 64, 2, false>}},
+        {{0, 256, (const void *)shared_mfma_kernel<1, KVD, 4, 2, 1, true>},
+         {1, 256, (const void *)shared_mfma_kernel<2, KVD, 4, 2, 1, true>},
+         {2, 256, (const void *)shared_lds_kernel<1, 4, KVD, 2, MIXED_KT, 1, true>},
+         {3, 256, (const void *)shared_lds_kernel<2, 4, KVD, 2, MIXED_KT, 1, true>},
+         {4, 512, (const void *)shared_lds_kernel<2, 8, KVD, 2, 64, 2, true>}},
     };
+    const bool split = a.nsplit > 1;
     static const bool mixed = [] {
         const char *e = std::getenv("MOSKA_SHARED_MIXED");
         return !(e && e[0] == '0');
@@ -38,7 +46,7 @@ int launch_shared_classes(const moska_problem_t &p, const SharedArgs &a, const S
     for (int c = pl.cmax; c >= pl.cmin && c > top; --c) {
         const int64_t bound = class_bound(p, pl, c);
         if (bound == 0) continue;
-        const SharedKernel &sk = table[c];
+        const SharedKernel &sk = table[split][c];
         const unsigned grid = (unsigned)(((bound + 7) / 8) * 8);
         int cls = c;
         void *kargs[] = {&args, &cls, &Hq, &Hkv, &C, &L, &k, &scale};
@@ -51,8 +59,9 @@ int launch_shared_classes(const moska_problem_t &p, const SharedArgs &a, const S
         if (c0 <= c1 && bound > 0) {
             const unsigned grid = (unsigned)(((bound + 7) / 8) * 8);
             void *kargs[] = {&args, &c0, &c1, &Hq, &Hkv, &C, &L, &k, &scale};
-            if (hipLaunchKernel((const void *)shared_mixed_kernel<KVD, 2>, dim3(grid, a.nsplit), dim3(256), kargs, 0, s) !=
-                hipSuccess)
+            const void *mk = split ? (const void *)shared_mixed_kernel<KVD, 2, true>
+                                   : (const void *)shared_mixed_kernel<KVD, 2, false>;
+            if (hipLaunchKernel(mk, dim3(grid, a.nsplit), dim3(256), kargs, 0, s) != hipSuccess)
                 return MOSKA_ERR_HIP;
         }
     }
