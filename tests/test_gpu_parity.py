@@ -51,6 +51,8 @@ SMALL = {
     "bf16-t2-split-unique-ragged": P(T=2, B=2, Hq=8, Hkv=2, C=4, L=64, k=2, U=3000),
     "fp8-t4": P(kv_dtype="fp8", T=4, B=6, Hq=16, Hkv=2, C=4, L=128, k=2, U=70),
     "f32-t3-ragged": P(q_dtype="f32", kv_dtype="f32", T=3, B=4, Hq=6, Hkv=3, D=64, C=5, L=60, k=2, U=50),
+    # more (KV head, chunk) buckets than the tile-list kernel stages in LDS (16 384 > 15 360), most of them empty
+    "bf16-many-buckets": P(B=40, Hq=16, Hkv=8, C=2048, L=32, k=3, U=40),
     # head sizes 256 (widest matrix-core routing kernel) and 48 (vector-ALU routing kernel)
     "bf16-d256": P(D=256, B=19, Hq=8, Hkv=2, C=21, L=70, k=3, U=20),
     "f32-d256": P(q_dtype="f32", kv_dtype="f32", D=256, B=5, Hq=4, Hkv=2, C=18, L=40, k=2, U=10),
