@@ -55,7 +55,10 @@ int shared_splits(const moska_problem_t &p) {
     const int64_t items = (int64_t)p.B * q_len(p) * p.Hkv * p.k, nb = (int64_t)p.Hkv * p.C;
     const int64_t nbe = items < nb ? items : nb;            // buckets that can be non-empty
     if (nbe > 256 || p.L < 1024) return 1;                  // one workgroup per compute unit already
-    int64_t n = (512 + nbe - 1) / nbe;                      // aim at ~512 workgroups ...
+    // tiles hold at most 256 rows, so many rows in few buckets also mean many workgroups
+    const int64_t by_rows = items * (p.Hq / p.Hkv) / 256;
+    const int64_t wgs = nbe > by_rows ? nbe : by_rows;      // workgroups the launch has at least
+    int64_t n = (512 + wgs - 1) / wgs;                      // aim at ~512 workgroups ...
     if (n > p.L / 512) n = p.L / 512;                       // ... of at least 512 keys each
     if (n > 16) n = 16;
     return n < 1 ? 1 : (int)n;
