@@ -51,6 +51,10 @@ SMALL = {
     "bf16-t2-split-unique-ragged": P(T=2, B=2, Hq=8, Hkv=2, C=4, L=64, k=2, U=3000),
     "fp8-t4": P(kv_dtype="fp8", T=4, B=6, Hq=16, Hkv=2, C=4, L=128, k=2, U=70),
     "f32-t3-ragged": P(q_dtype="f32", kv_dtype="f32", T=3, B=4, Hq=6, Hkv=3, D=64, C=5, L=60, k=2, U=50),
+    # degenerate sizes: one request, one head, one chunk of one token, one unique token
+    "bf16-single": P(B=1, Hq=1, Hkv=1, C=1, L=1, k=1, U=1),
+    "f32-single": P(q_dtype="f32", kv_dtype="f32", B=1, Hq=1, Hkv=1, D=16, C=1, L=1, k=1, U=1),
+    "fp8-single-request": P(kv_dtype="fp8", B=1, Hq=8, Hkv=2, C=3, L=33, k=2, U=7),
     # more (KV head, chunk) buckets than the tile-list kernel stages in LDS (16 384 > 15 360), most of them empty
     "bf16-many-buckets": P(B=40, Hq=16, Hkv=8, C=2048, L=32, k=3, U=40),
     # head sizes 256 (widest matrix-core routing kernel) and 48 (vector-ALU routing kernel)
