@@ -78,6 +78,40 @@ def test_small_problem_matches_oracle(name):
     check_against_oracle(generate(p, seed=101, unique_len=ragged), name)
 
 
+def _random_problem(rng):
+    """A small problem with sizes drawn around the tile, stage and group boundaries of the kernels."""
+    dt = rng.choice(["bf16", "bf16", "fp8", "f32"])
+    G, Hkv = rng.choice([1, 2, 3, 4, 6, 8, 16]), rng.choice([1, 2, 3, 4, 8])
+    D = 128 if dt != "f32" else rng.choice([16, 32, 64, 128])
+    if dt == "bf16" and rng.random() < 0.15:
+        D = rng.choice([48, 64, 256])
+    C = rng.choice([1, 2, 3, 5, 8, 17, 40])
+    k = rng.randint(1, min(C, 5))
+    L = rng.choice([1, 7, 31, 32, 33, 64, 100, 129, 300, 1100, 2500])
+    U = rng.choice([0, 1, 5, 33, 64, 150, 700])
+    T = rng.choice([1, 1, 1, 2, 3, 5])
+    B = rng.choice([1, 2, 3, 9, 30, 70, 150, 400])
+    if dt == "f32":
+        B, L, U = min(B, 9), min(L, 300), min(U, 150)
+    while B * T * G * Hkv * (k * L + U) * D > 1.5e9 and B > 1:       # keeps the oracle to well under a second
+        B = max(1, B // 2)
+    return Problem(B=B, Hq=G * Hkv, Hkv=Hkv, D=D, C=C, L=L, k=k, U=max(U, T if U else 0), T=T,
+                   q_dtype="f32" if dt == "f32" else "bf16", kv_dtype=dt,
+                   popularity=rng.choice(["uniform", "zipf"]), zipf_s=1.5, scale=rng.choice([1.0, 1.0, 0.5]))
+
+
+def test_random_small_problems():
+    # 80 seeded random shapes (dtypes, group sizes, head sizes, ragged contexts, several tokens per
+    # request, skewed popularity): every one against the oracle
+    import random
+    rng = random.Random(20251106)
+    for i in range(80):
+        p = _random_problem(rng)
+        ragged = rng.choice(["full", "ragged"])
+        print(f"random case {i}: {p} {ragged}", flush=True)
+        check_against_oracle(generate(p, seed=3000 + i, unique_len=ragged), f"random{i}")
+
+
 def test_config0_matches_stored_oracle_values():
     # expected values stored by tests/golden/make_config0_golden.py (oracle only)
     from test_oracle_pins import read_config0_golden
