@@ -29,11 +29,6 @@ __device__ __forceinline__ double key_to_score(uint64_t k) {
     return __longlong_as_double((long long)u);
 }
 
-// true if (ka,ca) should be selected before (kb,cb)
-__device__ __forceinline__ bool before(uint64_t ka, int ca, uint64_t kb, int cb) {
-    return ka > kb || (ka == kb && ca < cb);
-}
-
 // elements of a 16-byte load
 template <int QD> constexpr int epl() { return QD == MOSKA_BF16 ? 8 : 4; }
 
@@ -120,8 +115,44 @@ __global__ __launch_bounds__(256) void route_score_kernel(const void *__restrict
     }
 }
 
+// Wave-wide reductions that leave the result in every lane, on the vector ALU alone: two quad
+// permutes, two mirrors inside a row of 16 lanes (DPP), then the xor-16 / xor-32 pairs through
+// v_permlane16_swap / v_permlane32_swap.  (Six ds_bpermute rounds cost several times as much.)
+template <int CTRL> __device__ __forceinline__ uint32_t dpp(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL> __device__ __forceinline__ uint64_t dpp64(uint64_t v) {
+    return ((uint64_t)dpp<CTRL>((uint32_t)(v >> 32)) << 32) | dpp<CTRL>((uint32_t)v);
+}
+__device__ __forceinline__ uint64_t max_u64(uint64_t a, uint64_t b) { return a > b ? a : b; }
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+    v = max_u64(v, dpp64<0xB1>(v));                        // quad_perm [1,0,3,2]
+    v = max_u64(v, dpp64<0x4E>(v));                        // quad_perm [2,3,0,1]
+    v = max_u64(v, dpp64<0x141>(v));                       // row_half_mirror
+    v = max_u64(v, dpp64<0x140>(v));                       // row_mirror
+    const uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    auto l16 = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+    auto h16 = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+    v = max_u64(((uint64_t)h16[0] << 32) | l16[0], ((uint64_t)h16[1] << 32) | l16[1]);
+    const uint32_t lo2 = (uint32_t)v, hi2 = (uint32_t)(v >> 32);
+    auto l32 = __builtin_amdgcn_permlane32_swap(lo2, lo2, false, false);
+    auto h32 = __builtin_amdgcn_permlane32_swap(hi2, hi2, false, false);
+    return max_u64(((uint64_t)h32[0] << 32) | l32[0], ((uint64_t)h32[1] << 32) | l32[1]);
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+    v = min(v, dpp<0xB1>(v));
+    v = min(v, dpp<0x4E>(v));
+    v = min(v, dpp<0x141>(v));
+    v = min(v, dpp<0x140>(v));
+    auto a = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = min(a[0], a[1]);
+    auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return min(b[0], b[1]);
+}
+
 // The k best of the wave's C keys (in LDS), written to ids/scores of row o = (b*Hkv + h).
-// Each lane remembers the best of its own chunks; only the round's winner rescans.
+// Each lane remembers the best of its own chunks; a round takes the largest key of the wave and,
+// among the lanes that hold it, the lowest chunk id; only the round's winner rescans.
 __device__ __forceinline__ void select_topk(uint64_t *keys, int C, int k, int lane, bool active, int64_t o,
                                             int32_t *__restrict__ ids, float *__restrict__ scores) {
     auto rescan = [&](uint64_t &bk, int &bc) {
@@ -136,14 +167,8 @@ __device__ __forceinline__ void select_topk(uint64_t *keys, int C, int k, int la
     int bc;
     rescan(bk, bc);
     for (int t = 0; t < k; ++t) {
-        uint64_t wk = bk;
-        int wc = bc;
-#pragma unroll
-        for (int m = 1; m < kWave; m <<= 1) {
-            const uint64_t ok = __shfl_xor(wk, m);
-            const int oc = __shfl_xor(wc, m);
-            if (before(ok, oc, wk, wc)) { wk = ok; wc = oc; }
-        }
+        const uint64_t wk = wave_max_u64(bk);
+        const int wc = (int)wave_min_u32(bk == wk ? (uint32_t)bc : 0x7FFFFFFFu);
         if (lane == (wc & (kWave - 1))) {
             keys[wc] = 0;
             rescan(bk, bc);
@@ -168,6 +193,41 @@ __global__ __launch_bounds__(256) void route_select_kernel(const uint64_t *__res
     for (int c = lane; c < C; c += kWave) keys[c] = gkeys[r * C + c];
     __syncthreads();
     select_topk(keys, C, k, lane, active, r, ids, scores);
+}
+
+// The same selection with the keys in registers (up to 64*KPL chunks: lane l holds chunks l, l+64, ...):
+// no LDS, no divergent rescans -- every lane re-derives its best key from its KPL registers each round.
+template <int KPL>
+__global__ __launch_bounds__(256) void route_select_reg_kernel(const uint64_t *__restrict__ gkeys,
+                                                                int32_t *__restrict__ ids, float *__restrict__ scores,
+                                                                int64_t rows, int C, int k) {
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int64_t r = (int64_t)blockIdx.x * 4 + wave;      // r = b*Hkv + h
+    if (r >= rows) return;
+    uint64_t key[KPL];
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) {
+        const int c = lane + kWave * i;
+        key[i] = c < C ? gkeys[r * C + c] : 0;             // 0 is below every real key
+    }
+    for (int t = 0; t < k; ++t) {
+        uint64_t bk = key[0];
+        int bi = 0;
+#pragma unroll
+        for (int i = 1; i < KPL; ++i) {
+            if (key[i] > bk) { bk = key[i]; bi = i; }      // equal keys: the lower chunk id stays
+        }
+        const uint64_t wk = wave_max_u64(bk);
+        const int wc = (int)wave_min_u32(bk == wk ? (uint32_t)(lane + kWave * bi) : 0x7FFFFFFFu);
+#pragma unroll
+        for (int i = 0; i < KPL; ++i) {
+            if (wc == lane + kWave * i) key[i] = 0;
+        }
+        if (lane == 0) {
+            ids[r * k + t] = wc;
+            if (scores) scores[r * k + t] = (float)key_to_score(wk);
+        }
+    }
 }
 
 // Vector-ALU scoring for the other head sizes: one wave per (request, KV head), lane l scores
@@ -236,6 +296,20 @@ int launch_route(const moska_problem_t &p, const void *Q, const void *E, int32_t
         if (hipLaunchKernel(score, dim3((unsigned)((waves + 3) / 4)), dim3(256), kargs, 0, s) != hipSuccess)
             return MOSKA_ERR_HIP;
 
+        if (p.C <= 16 * kWave) {                           // keys fit in registers
+            const int kpl = (p.C + kWave - 1) / kWave;
+            const void *sel = kpl <= 1 ? (const void *)route_select_reg_kernel<1>
+                              : kpl <= 2 ? (const void *)route_select_reg_kernel<2>
+                              : kpl <= 4 ? (const void *)route_select_reg_kernel<4>
+                              : kpl <= 8 ? (const void *)route_select_reg_kernel<8>
+                                         : (const void *)route_select_reg_kernel<16>;
+            int64_t nrows = rows;
+            const uint64_t *ck = keys;
+            void *sargs[] = {&ck, &ids, &scores, &nrows, &C, &k};
+            if (hipLaunchKernel(sel, dim3((unsigned)((rows + 3) / 4)), dim3(4 * kWave), sargs, 0, s) != hipSuccess)
+                return MOSKA_ERR_HIP;
+            return hip_status(hipGetLastError());
+        }
         const size_t per_wave = (size_t)p.C * sizeof(uint64_t);
         int W = (int)((140u * 1024u) / per_wave);
         if (W < 1) return MOSKA_ERR_UNSUPPORTED;
