@@ -55,14 +55,19 @@ __global__ __launch_bounds__(1024) void bucket_kernel(const int32_t *__restrict_
     const int lo = wave * slice, hi = min(n, lo + slice);
     int *myhist = hist + wave * C;
     const uint64_t below = (1ull << lane) - 1ull;
+    // chunk id of item i of this head (0 past the slice); the next batch's ids are requested before the
+    // current batch is worked on, so that a batch does not start with a global-memory round trip
+    auto id_of = [&](int i) {
+        if (i >= hi) return 0;
+        const int b = i / k, j = i - b * k;
+        return ids[((int64_t)b * Hkv + h) * k + j];
+    };
+    int cnext = id_of(lo + lane);
     for (int i0 = lo; i0 < hi; i0 += kWave) {
         const int i = i0 + lane;
         const bool valid = i < hi;
-        int c = 0;
-        if (valid) {
-            const int b = i / k, j = i - b * k;
-            c = ids[((int64_t)b * Hkv + h) * k + j];
-        }
+        const int c = cnext;
+        cnext = id_of(i + kWave);
         uint64_t peers = __ballot(valid);
         for (int bit = 0; bit < nbits; ++bit) {
             const bool one = (c >> bit) & 1;
@@ -103,13 +108,14 @@ __global__ __launch_bounds__(1024) void bucket_kernel(const int32_t *__restrict_
     if (threadIdx.x == 0 && h == Hkv - 1) off[Hkv * C] = Hkv * n;
     __syncthreads();
 
+    cnext = id_of(lo + lane);
+    int rnext = lo + lane < hi ? rank[(int64_t)h * n + lo + lane] : 0;
     for (int i0 = lo; i0 < hi; i0 += kWave) {
         const int i = i0 + lane;
-        if (i < hi) {
-            const int b = i / k, j = i - b * k;
-            const int c = ids[((int64_t)b * Hkv + h) * k + j];
-            items[(int64_t)h * n + coff[c] + myhist[c] + rank[(int64_t)h * n + i]] = i;
-        }
+        const int c = cnext, r = rnext;
+        cnext = id_of(i + kWave);
+        rnext = i + kWave < hi ? rank[(int64_t)h * n + i + kWave] : 0;
+        if (i < hi) items[(int64_t)h * n + coff[c] + myhist[c] + r] = i;
     }
 }
 
