@@ -24,11 +24,13 @@ struct SharedPlan {
 SharedPlan shared_plan(const moska_problem_t &p);
 
 // Upper bound on the number of tiles of class c (host-known, sizes the launch grid): a remainder
-// tile of class c > cmin holds more than kClassRows[c-1] rows and a bucket has at most one.
+// tile of class c > cmin holds more than kClassRows[c-1] rows and a bucket has at most one; a bucket
+// holds at most one item per query token, i.e. B*G rows, so small batches have no large tiles at all.
 inline int64_t class_bound(const moska_problem_t &p, const SharedPlan &pl, int c) {
     if (c < pl.cmin || c > pl.cmax) return 0;
     const int64_t items = (int64_t)p.B * p.Hkv * p.k, nb = (int64_t)p.Hkv * p.C;
     const int64_t rows = items * (p.Hq / p.Hkv);
+    if (c > pl.cmin && (int64_t)p.B * (p.Hq / p.Hkv) <= class_rows(c - 1)) return 0;
     const int64_t nbe = items < nb ? items : nb;
     int64_t rem = c == pl.cmin ? nbe : rows / (class_rows(c - 1) + 1);
     if (rem > nbe) rem = nbe;
