@@ -5,11 +5,14 @@ A step is one pass of the whole path (route -> bucket -> shared attention -> uni
 merge) over one batch of synthetic requests, inputs resident in HBM.  Default workload: the
 configuration the headline metric is quoted on (batch 256, 1M shared tokens, bf16).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config i] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config i] [--no-cpu-baseline] [--no-extra-configs]
 
 Prints one JSON line: decode queries/s (value), shared-attention TFLOP/s, per-call times with
-their roofline fractions, the roofline object of the slowest call and the CPU oracle's rate on a
-bounded sample of the same workload.
+their roofline fractions, the roofline object of the slowest call, the CPU oracle's rate on a
+bounded sample of the same workload and, under "configs", a short measurement of the two larger
+benchmark configurations (3: 4M shared tokens, Zipf popularity; 4: fp8 store, 64 query heads).
+
+    python bench.py --calibrate      a plain 1 GiB device copy, for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE
 """
 import argparse
 import json
@@ -154,51 +157,9 @@ def reuse_sweep(steps, warmup):
             torch.cuda.empty_cache()
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="workload index (2 = the headline configuration)")
-    ap.add_argument("--q-len", type=int, default=1,
-                    help="query tokens per request: the same number of query tokens from B/q_len requests")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=0, help="requests in the oracle's sample (0 = auto)")
-    ap.add_argument("--reuse-sweep", action="store_true",
-                    help="shared attention against rows per bucket (16..4096) instead of the decode step")
-    ap.add_argument("--paper-sweep", action="store_true",
-                    help="instead of the benchmark line: utilisation against batch size at the paper's operating point")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (no sharding or collectives are part of it); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-    import paper_2511_06010_amd as moska
-    from moska_inputs import config, generate
-
-    moska.load_library()                       # fails loudly if the HIP library is not built
-    if args.reuse_sweep:
-        assert torch.cuda.is_available(), "bench.py needs a GPU"
-        torch.cuda.set_device(0)
-        reuse_sweep(args.steps, args.warmup)
-        return
-    if args.paper_sweep:
-        assert torch.cuda.is_available(), "bench.py needs a GPU"
-        torch.cuda.set_device(0)
-        paper_sweep(args.steps, args.warmup)
-        return
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    p = config(args.config)
-    if args.q_len > 1:
-        assert p.B % args.q_len == 0, "q_len must divide the batch size"
-        p = p.with_(T=args.q_len, B=p.B // args.q_len, name=p.name + f"-qlen{args.q_len}")
-    inp = generate(p, seed=20251106 + args.config, device="cuda")
-    buf = moska.Buffers(p)
-    torch.cuda.synchronize()
-
+def time_step(moska, torch, p, inp, buf, steps, warmup):
+    """W warm-up and K timed passes of the five calls on torch's current stream (the stream every call
+    is enqueued on), with HIP events between the calls.  Returns (ms per step, {call: sorted ms})."""
     calls = ["route", "bucket", "shared_attn", "unique_attn", "merge"]
 
     def step(events=None):
@@ -216,21 +177,128 @@ def main():
         moska.merge(p, buf.part_O, buf.part_LSE, buf.O, buf.LSE)
         rec(5)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
-    # events live on torch's current stream, the stream every call is enqueued on
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(evs[i])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
     samples = {c: sorted(e[i].elapsed_time(e[i + 1]) for e in evs) for i, c in enumerate(calls)}
+    return (t1 - t0) * 1e3 / steps, samples
+
+
+def kernel_table(p, bucket_off, samples):
+    """Per call: mean / median / min time, achieved GB/s and TFLOP/s of ALGORITHMIC work, roofline fractions."""
+    work = algorithmic_work(p, bucket_off)
+    kernels = {}
+    for c, v in samples.items():
+        ms = sum(v) / len(v)
+        gbs = work[c]["bytes"] / (ms * 1e-3) / 1e9
+        tfl = work[c]["flops"] / (ms * 1e-3) / 1e12
+        kernels[c] = {"ms": round(ms, 5), "ms_median": round(v[len(v) // 2], 5), "ms_min": round(v[0], 5),
+                      "GB/s": round(gbs, 1), "TFLOP/s": round(tfl, 2), "hbm_frac": round(gbs / HBM_PEAK_GBS, 4),
+                      "mfma_frac": round(tfl / MFMA_BF16_PEAK_TFLOPS, 4)}
+    att_s = shared_attainable_s(p, bucket_off)
+    kernels["shared_attn"]["roofline_ms"] = round(att_s * 1e3, 5)          # sum over buckets of max(HBM, MFMA) time
+    kernels["shared_attn"]["of_roofline"] = round(att_s * 1e3 / kernels["shared_attn"]["ms"], 4)
+    return kernels, work
+
+
+def extra_config(moska, torch, idx, steps, warmup):
+    """A short measurement of another benchmark configuration, for the "configs" object."""
+    from moska_inputs import config, generate
+    p = config(idx)
+    inp = generate(p, seed=20251106 + idx, device="cuda")
+    buf = moska.Buffers(p)
+    torch.cuda.synchronize()
+    ms, samples = time_step(moska, torch, p, inp, buf, steps, warmup)
+    kernels, _ = kernel_table(p, buf.bucket_off.cpu(), samples)
+    sh, un = kernels["shared_attn"], kernels["unique_attn"]
+    out = {"workload": p.name, "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 4),
+           "queries_per_s": round(p.Bq / (ms * 1e-3), 1),
+           "shared_ms": sh["ms"], "shared_TFLOPs": sh["TFLOP/s"], "shared_mfma_frac": sh["mfma_frac"],
+           "shared_of_attainable": sh["of_roofline"], "shared_GBs": sh["GB/s"], "shared_hbm_frac": sh["hbm_frac"],
+           "unique_ms": un["ms"], "unique_GBs": un["GB/s"], "unique_hbm_frac": un["hbm_frac"],
+           "route_ms": kernels["route"]["ms"], "bucket_ms": kernels["bucket"]["ms"], "merge_ms": kernels["merge"]["ms"]}
+    del inp, buf
+    torch.cuda.empty_cache()
+    return out
+
+
+def calibrate():
+    """A plain device-to-device copy of 1 GiB (torch's copy kernel), 10 times: its FETCH_SIZE and
+    WRITE_SIZE under `rocprofv3 --pmc` against the known 1 GiB each way give the factors by which the
+    counters of the attention kernels are scaled; also prints the copy's own rate."""
+    import torch
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 10
+    print(json.dumps({"calibration_copy_bytes": n, "ms": round(ms, 4), "GB/s_each_way": round(n / ms / 1e6, 1)}))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="workload index (2 = the headline configuration)")
+    ap.add_argument("--q-len", type=int, default=1,
+                    help="query tokens per request: the same number of query tokens from B/q_len requests")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra-configs", action="store_true",
+                    help="skip the short measurement of configurations 3 and 4 that follows the headline one")
+    ap.add_argument("--cpu-sample", type=int, default=0, help="requests in the oracle's sample (0 = auto)")
+    ap.add_argument("--reuse-sweep", action="store_true",
+                    help="shared attention against rows per bucket (16..4096) instead of the decode step")
+    ap.add_argument("--paper-sweep", action="store_true",
+                    help="instead of the benchmark line: utilisation against batch size at the paper's operating point")
+    ap.add_argument("--calibrate", action="store_true", help="run the 1 GiB calibration copy and exit")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding or collectives are part of it); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2511_06010_amd as moska
+    from moska_inputs import config, generate
+
+    moska.load_library()                       # fails loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.calibrate:
+        calibrate()
+        return
+    if args.reuse_sweep:
+        reuse_sweep(args.steps, args.warmup)
+        return
+    if args.paper_sweep:
+        paper_sweep(args.steps, args.warmup)
+        return
+    p = config(args.config)
+    if args.q_len > 1:
+        assert p.B % args.q_len == 0, "q_len must divide the batch size"
+        p = p.with_(T=args.q_len, B=p.B // args.q_len, name=p.name + f"-qlen{args.q_len}")
+    inp = generate(p, seed=20251106 + args.config, device="cuda")
+    buf = moska.Buffers(p)
+    torch.cuda.synchronize()
+
+    ms_per_step, samples = time_step(moska, torch, p, inp, buf, args.steps, args.warmup)
     per_call_ms = {c: sum(v) / len(v) for c, v in samples.items()}
 
-    # the same step through the single entry point (it may overlap unique attention with the rest)
+    # the same step through the single entry point (the same five launches in the same order)
     def fused():
         moska.decode_step(p, inp.Q, inp.E, inp.Ks, inp.Vs, inp.scale_k, inp.scale_v, inp.Ku, inp.Vu, inp.unique_len,
                           buf.ids, buf.bucket_off, buf.bucket_items, buf.part_O, buf.part_LSE, buf.O, buf.LSE, buf.ws)
@@ -257,16 +325,18 @@ def main():
     graph_ms = (time.perf_counter() - g0) * 1e3 / args.steps
 
     # the five calls again on two streams (same priority): the latency-bound routing and bucketing run
-    # beside unique attention, which does not depend on them; shared attention waits for both
+    # beside unique attention, which does not depend on them; shared attention waits for both.  The side
+    # stream has a workspace of its own (calls on different streams must not share one).
     side = torch.cuda.Stream()
     fork, join = torch.cuda.Event(), torch.cuda.Event()
+    side_ws = torch.empty_like(buf.ws)
 
     def two_streams():
         fork.record()
         with torch.cuda.stream(side):
             side.wait_event(fork)
-            moska.route(p, inp.Q, inp.E, buf.ids, None, buf.ws)
-            moska.bucket(p, buf.ids, buf.bucket_off, buf.bucket_items, buf.ws)
+            moska.route(p, inp.Q, inp.E, buf.ids, None, side_ws)
+            moska.bucket(p, buf.ids, buf.bucket_off, buf.bucket_items, side_ws)
             join.record()
         moska.unique_attn(p, inp.Q, inp.Ku, inp.Vu, inp.unique_len, buf.part_O, buf.part_LSE, buf.ws)
         torch.cuda.current_stream().wait_event(join)
@@ -281,19 +351,9 @@ def main():
         two_streams()
     torch.cuda.synchronize()
     two_stream_ms = (time.perf_counter() - s0) * 1e3 / args.steps
+    del side_ws
 
-    work = algorithmic_work(p, buf.bucket_off.cpu())
-    kernels = {}
-    for c in calls:
-        ms = per_call_ms[c]
-        gbs = work[c]["bytes"] / (ms * 1e-3) / 1e9
-        tfl = work[c]["flops"] / (ms * 1e-3) / 1e12
-        kernels[c] = {"ms": round(ms, 5), "ms_median": round(samples[c][len(samples[c]) // 2], 5),
-                      "ms_min": round(samples[c][0], 5), "GB/s": round(gbs, 1), "TFLOP/s": round(tfl, 2),
-                      "hbm_frac": round(gbs / HBM_PEAK_GBS, 4), "mfma_frac": round(tfl / MFMA_BF16_PEAK_TFLOPS, 4)}
-    att_s = shared_attainable_s(p, buf.bucket_off.cpu())
-    kernels["shared_attn"]["roofline_ms"] = round(att_s * 1e3, 5)          # sum over buckets of max(HBM, MFMA) time
-    kernels["shared_attn"]["of_roofline"] = round(att_s * 1e3 / per_call_ms["shared_attn"], 4)
+    kernels, work = kernel_table(p, buf.bucket_off.cpu(), samples)
     dom = max(("shared_attn", "unique_attn"), key=lambda c: per_call_ms[c])
     # both attention calls are bound by the bytes the method itself must stream at this workload
     # (arithmetic intensity ~ rows per bucket flop/B, far left of the 315 flop/B ridge)
@@ -342,6 +402,11 @@ def main():
                                "kind": "oracle", "seconds": round(c1 - c0, 2),
                                "sample": f"first {nb} of {p.B} requests, all {p.Hq} heads, full shared store; "
                                          f"max |GPU-oracle| on the sample {err:.2e}"}
+    if not args.no_extra_configs and args.config == 2 and args.q_len == 1:
+        # free the headline workload, then a few steps of the two larger configurations
+        del inp, buf
+        torch.cuda.empty_cache()
+        out["configs"] = {f"cfg{i}": extra_config(moska, torch, i, 5, 2) for i in (3, 4)}
     print(json.dumps(out))
 
 

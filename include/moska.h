@@ -94,7 +94,9 @@ int moska_route(const moska_problem_t *p, const void *Q, const void *E,
  * index b*k+j and falls into bucket h*C + ids[b,h,j].
  *   bucket_off [Hkv*C+1] int32 out: exclusive prefix sum of bucket sizes,
  *   bucket_items [B*Hkv*k] int32 out: the item indices of each bucket, ascending.
- * Deterministic, no atomics.  ids must hold values in [0,C).  ws: moska_workspace_bytes. */
+ * Deterministic, no atomics.  ids must hold values in [0,C); a chunk named twice for one (request,
+ * KV head) gives two items of the same bucket, each served through its own slot.
+ * ws: moska_workspace_bytes. */
 int moska_bucket(const moska_problem_t *p, const int32_t *ids,
                  int32_t *bucket_off, int32_t *bucket_items,
                  void *ws, size_t ws_bytes, void *stream);

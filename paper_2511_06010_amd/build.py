@@ -10,8 +10,6 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmoska.so")
-PROBE = os.path.join(PKG, "hbm_probe")
-MFMA_PROBE = os.path.join(PKG, "mfma_probe")
 SOURCES = ["attn_mfma_shared_bf16.hip", "attn_mfma_shared_fp8.hip", "attn_mfma.hip", "api.hip", "route.hip",
            "bucket.hip", "attn_generic.hip", "merge.hip", "cache_build.hip"]
 # packed-fp32 VALU forms are disabled on purpose (they have produced wrong results on the test machines)
@@ -36,12 +34,8 @@ def build_library(extra_flags=(), verbose: bool = True) -> str:
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
-    # stand-alone bandwidth / counter-calibration probe
-    subprocess.check_call(["hipcc", "-O3", "--offload-arch=gfx950", "-o", PROBE, os.path.join(CSRC, "hbm_probe.hip")])
-    # stand-alone instruction-rate probe built from the attention kernels' own inner-loop helpers
-    subprocess.check_call(["hipcc", *FLAGS, "-fno-honor-nans", "-o", MFMA_PROBE, os.path.join(CSRC, "mfma_probe.hip")])
     if verbose:
-        print(f"built {LIB}, {PROBE} and {MFMA_PROBE}")
+        print(f"built {LIB}")
     return LIB
 
 

@@ -6,31 +6,34 @@
 
 namespace moska {
 
+// Development builds (-DMOSKA_TUNING) take overrides of the launch heuristics from the environment, each
+// read once per process; the library as shipped reads no environment and holds no state.
+#ifdef MOSKA_TUNING
+int tuning_env(const char *name, int dflt) {
+    const char *e = std::getenv(name);
+    return e && *e ? std::atoi(e) : dflt;
+}
+#endif
+
 bool use_mfma_path(const moska_problem_t &p) {
-    static const bool force_generic = [] {
-        const char *e = std::getenv("MOSKA_FORCE_GENERIC");
-        return e && e[0] == '1';
-    }();
+    static const bool force_generic = tuning_env("MOSKA_FORCE_GENERIC", 0) == 1;
     return !force_generic && p.q_dtype == MOSKA_BF16 && p.D == 128;
 }
 
 SharedPlan shared_plan(const moska_problem_t &p) {
     if (!use_mfma_path(p)) return SharedPlan{0, 0};          // the vector-ALU kernel serves 16-row tiles
-    SharedPlan pl{0, kNumClasses - 1};
-    // tuning overrides: smallest / largest tile class (0..4 = 16, 32, 64, 128, 256 rows)
-    if (const char *e = std::getenv("MOSKA_SHARED_CMIN")) pl.cmin = std::atoi(e);
-    if (const char *e = std::getenv("MOSKA_SHARED_CMAX")) pl.cmax = std::atoi(e);
+    // smallest / largest tile class (0..4 = 16, 32, 64, 128, 256 rows)
+    static const int cmin_env = tuning_env("MOSKA_SHARED_CMIN", 0), cmax_env = tuning_env("MOSKA_SHARED_CMAX", kNumClasses - 1);
+    SharedPlan pl{cmin_env, cmax_env};
     if (pl.cmin < 0) pl.cmin = 0;
     if (pl.cmax > kNumClasses - 1) pl.cmax = kNumClasses - 1;
     if (pl.cmin > pl.cmax) pl.cmin = pl.cmax;
     return pl;
 }
 
-// tuning override: a positive integer in the named environment variable replaces the heuristic
+// a positive override replaces the heuristic
 static int env_splits(const char *name, int limit) {
-    const char *e = std::getenv(name);
-    if (!e) return 0;
-    const int v = std::atoi(e);
+    const int v = tuning_env(name, 0);
     return v < 1 ? 0 : v > limit ? limit : v;
 }
 

@@ -175,7 +175,7 @@ int set_lds(Kern kern, size_t lds) {
 int launch_shared_generic(const moska_problem_t &p, const SharedArgs &a, const SharedPlan &pl, hipStream_t s) {
     if (pl.cmin != 0 || pl.cmax != 0 || class_rows(0) != TR) return MOSKA_ERR_UNSUPPORTED;
     const size_t lds = generic_lds_bytes(p.D);
-    const unsigned grid = (unsigned)class_bound(p, pl, 0);
+    const unsigned grid = (unsigned)tiles_bound(p, pl, 0, 0);
     if (grid == 0) return MOSKA_OK;
     void (*kern)(SharedArgs, int, int, int, int, int, int, int, float) = nullptr;
     if (p.q_dtype == MOSKA_F32 && p.shared_kv_dtype == MOSKA_F32) kern = shared_generic_kernel<MOSKA_F32, MOSKA_F32>;

@@ -431,10 +431,10 @@ __device__ __forceinline__ void store_rows(const WaveState<NR> &st, int q, const
     }
 }
 
-// Merge the NW waves' states pairwise through LDS and write the rows (all threads of the
-// workgroup must call this: it contains barriers).
+// Merge the NW waves' states pairwise through LDS and write the rows (all NW*64 threads that share
+// `lds` must call this, tid = 0 .. NW*64-1: it contains workgroup barriers).
 template <int NR, int NW, bool NT>
-__device__ __forceinline__ void combine_and_store(WaveState<NR> &st, float *lds, int wave, int q, int x,
+__device__ __forceinline__ void combine_and_store(WaveState<NR> &st, float *lds, int tid, int wave, int q, int x,
                                                   const int64_t (&orow)[NR], float vmul, float *part_O,
                                                   float *part_LSE) {
     constexpr int R = 16 * NR;
@@ -499,8 +499,8 @@ __device__ __forceinline__ void combine_and_store(WaveState<NR> &st, float *lds,
         }
     }
     __syncthreads();
-    const int col = threadIdx.x & 31;
-    for (int rr = threadIdx.x >> 5; rr < R; rr += 2 * NW) {
+    const int col = tid & 31;
+    for (int rr = tid >> 5; rr < R; rr += 2 * NW) {
         const float *row = lds + rr * OSTRIDE;
         const int64_t o = *(const int64_t *)(row + HD + 2);
         if (o >= 0) store_partial16<NT>(part_O + o * HD + 4 * col, *(const f32x4 *)(row + 4 * col));
@@ -532,15 +532,15 @@ __device__ __forceinline__ int64_t shared_out_row(const SharedArgs &a, int64_t b
 }
 
 // Tile (bkt, row0) of Shared KV Attention on the streaming path: up to 16*NR gathered rows of
-// bucket bkt against (slice blockIdx.y of) its chunk.  comb: LDS for the cross-wave merge,
-// (NW/2)*16*NR*OSTRIDE floats.
+// bucket bkt against (slice blockIdx.y of) its chunk, by the NW*64 threads tid = 0 .. NW*64-1.
+// comb: their LDS for the cross-wave merge, (NW/2)*16*NR*OSTRIDE floats.
 template <int NR, int KVD, int NW, int AUX, int NKB, bool SPLIT>
 __device__ __forceinline__ void stream_tile(const SharedArgs &a, int bkt, int row0, int Hq, int Hkv, int C, int L,
-                                            int k, float scale, float *comb) {
+                                            int k, float scale, float *comb, int tid) {
     const int h = bkt / C, c = bkt - h * C, G = Hq / Hkv;
     const int beg = a.off[bkt], rows = (a.off[bkt + 1] - beg) * G;
-    const int lane = threadIdx.x & 63, q = lane >> 4, x = lane & 15;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps tile indices in SGPRs
+    const int lane = tid & 63, q = lane >> 4, x = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps tile indices in SGPRs
 
     uint32_t qf[NR][4][4];
     int64_t orow[NR];
@@ -567,34 +567,23 @@ __device__ __forceinline__ void stream_tile(const SharedArgs &a, int bkt, int ro
     WaveState<NR> st;
     attend<NR, KVD, NW, AUX, NKB>(st, qf, (const char *)a.Ks + base, (const char *)a.Vs + base, nk, nk, nk,
                                   scale * kmul * kLog2e, wave, q, x);
-    combine_and_store<NR, NW, !SPLIT>(st, comb, wave, q, x, orow, vmul, SPLIT ? a.split_O : a.part_O,
+    combine_and_store<NR, NW, !SPLIT>(st, comb, tid, wave, q, x, orow, vmul, SPLIT ? a.split_O : a.part_O,
                                       SPLIT ? a.split_LSE : a.part_LSE);
 }
 
-// Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of the tile
-// list so the tiles of one bucket (which re-read the same chunk) share an L2.  Returns the tile
-// index inside [0, ntiles) or -1 if this workgroup has none.
-__device__ __forceinline__ int xcd_tile_index(int ntiles) {
-    const int per = (ntiles + 7) >> 3, slot = blockIdx.x >> 3;
-    const int w = (blockIdx.x & 7) * per + slot;
-    return (slot >= per || w >= ntiles) ? -1 : w;
+// Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of the work
+// list so the tiles of one bucket (which re-read the same chunk) share an L2.  bx: the workgroup's
+// number inside a range of workgroups that starts at a multiple of 8.  Returns the work item
+// inside [0, n) or -1 if this workgroup has none.
+__device__ __forceinline__ int xcd_tile_index(int bx, int n) {
+    const int per = (n + 7) >> 3, slot = bx >> 3;
+    const int w = (bx & 7) * per + slot;
+    return (slot >= per || w >= n) ? -1 : w;
 }
 
 // Up to 32 rows fit in 256 registers per lane: asking for two waves per SIMD keeps the MFMA
 // accumulators in architectural VGPRs, where the softmax rescale can touch them without copies.
 constexpr int min_waves(int NR) { return NR == 1 ? 3 : NR == 2 ? 2 : 1; }
-
-// One size class of the tile list, streaming path.
-template <int NR, int KVD, int NW, int AUX, int NKB, bool SPLIT>
-__global__ __launch_bounds__(NW * 64, min_waves(NR)) void shared_mfma_kernel(SharedArgs a, int cls, int Hq, int Hkv,
-                                                                              int C, int L, int k, float scale) {
-    __shared__ float comb[(NW / 2) * 16 * NR * OSTRIDE];
-    const int first = a.tile_hdr[cls];
-    const int w = xcd_tile_index(a.tile_hdr[cls + 1] - first);
-    if (w < 0) return;
-    stream_tile<NR, KVD, NW, AUX, NKB, SPLIT>(a, a.tiles[2 * (first + w)], a.tiles[2 * (first + w) + 1], Hq, Hkv, C, L, k,
-                                       scale, comb);
-}
 
 // Unique KV Attention: a workgroup serves (up to 16*NR of) the T*G query rows of one (request, KV
 // head) pair -- row t*G + g is query token t, head g of the group -- over one of nsplit contiguous
@@ -633,7 +622,7 @@ __global__ __launch_bounds__(NW * 64, min_waves(NR)) void unique_mfma_kernel(Uni
     WaveState<NR> st;
     attend<NR, MOSKA_BF16, NW, AUX, NKB>(st, qf, (const char *)a.Ku + base, (const char *)a.Vu + base, nkeys, nsafe, lim,
                                          scale * kLog2e, wave, q, x);
-    combine_and_store<NR, NW, !SPLIT>(st, comb, wave, q, x, orow, 1.f, SPLIT ? a.split_O : a.part_O,
+    combine_and_store<NR, NW, !SPLIT>(st, comb, threadIdx.x, wave, q, x, orow, 1.f, SPLIT ? a.split_O : a.part_O,
                                       SPLIT ? a.split_LSE : a.part_LSE);
 }
 

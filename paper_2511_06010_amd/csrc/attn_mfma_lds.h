@@ -125,20 +125,21 @@ __device__ __forceinline__ void pv_from_lds(WaveState<NR> &st, const uint4 *lv, 
 // LDS footprint of a tile kernel, in uint4 units: two buffers of K and V stages
 template <int KT> constexpr int lds_units() { return 4 * KT * 16; }
 
-// Tile (bkt, row0) on the LDS-staged path: 16*NR*NWV rows.  smem: lds_units<KT>() uint4.
+// Tile (bkt, row0) on the LDS-staged path: 16*NR*NWV rows, by the NWV*64 threads tid = 0 .. NWV*64-1
+// that share smem (lds_units<KT>() uint4).  Contains one workgroup barrier per stage plus one.
 // KT keys per stage (32 or 64); PD stages of global loads are kept in flight in registers (1, 2 or 4):
 // the loads of stage t+1+PD are issued when stage t+1 has been copied to LDS, so they have PD
 // stages of MFMA work to land.
 template <int NR, int NWV, int KVD, int AUX, int KT, int PD, bool SPLIT>
 __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0, int Hq, int Hkv, int C, int Lchunk,
-                                         int k, float scale, uint4 *smem) {
+                                         int k, float scale, uint4 *smem, int tid) {
     static_assert(KT == 32 || KT == 64, "keys per stage");
     static_assert(PD == 1 || PD == 2 || PD == 4, "stages in flight");
     constexpr int T = NWV * 64;
     constexpr int SU = KT * 16;                            // uint4 units of K (or V) per stage
     uint4 *ldsK = smem, *ldsV = smem + 2 * SU;
     const int h = bkt / C, c = bkt - h * C, G = Hq / Hkv;
-    const int tid = threadIdx.x, lane = tid & 63, q = lane >> 4, x = lane & 15;
+    const int lane = tid & 63, q = lane >> 4, x = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     // this workgroup's keys: L of them from first_key on (the whole chunk unless chunks are split over
@@ -235,43 +236,53 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
     store_rows<NR, !SPLIT>(st, q, orow, vmul, SPLIT ? a.split_O : a.part_O, SPLIT ? a.split_LSE : a.part_LSE);
 }
 
-constexpr int lds_min_waves(int NR) { return NR >= 4 ? 1 : 2; }
-
-// One size class of the tile list, LDS-staged path.
-template <int NR, int NWV, int KVD, int AUX, int KT, int PD, bool SPLIT>
-__global__ __launch_bounds__(NWV * 64, lds_min_waves(NR)) void shared_lds_kernel(SharedArgs a, int cls, int Hq, int Hkv,
-                                                                                  int C, int L, int k, float scale) {
-    __shared__ uint4 smem[lds_units<KT>()];
-    const int first = a.tile_hdr[cls];
-    const int w = xcd_tile_index(a.tile_hdr[cls + 1] - first);
-    if (w < 0) return;
-    lds_tile<NR, NWV, KVD, AUX, KT, PD, SPLIT>(a, a.tiles[2 * (first + w)], a.tiles[2 * (first + w) + 1], Hq, Hkv, C, L, k,
-                                        scale, smem);
-}
-
-// Classes [c0, c1] (at most 128 rows, all within 256 registers per lane) in ONE launch, so that
-// sparsely populated classes do not each pay a kernel's fill and drain.  The tile list is walked
-// from its end: the largest tiles start first.
-constexpr int MIXED_KT = 64;       // keys per LDS stage of the mixed launch (64 KiB of stages per workgroup)
-
+// The whole tile list in ONE launch of 512-thread workgroups, so that no size class pays a kernel's
+// fill and drain of its own and the long 256-row tiles run beside the streaming ones.  Three ranges
+// of workgroups, each a multiple of 8 long, largest tiles first:
+//   [0, nb4)            one 256-row tile per workgroup (8 waves x 32 rows)
+//   [nb4, nb4 + nbL)    two LDS-staged tiles of up to 128 rows per workgroup, one per half (4 waves
+//                       each, with its own half of the LDS); both halves stream chunks of the same
+//                       length, so they execute the same number of workgroup barriers
+//   the rest            (fp8 store) two streaming tiles of up to 32 rows, one per half: an fp8 store
+//                       streams them (each wave its own keys, twice the bytes in flight of an fp8 LDS
+//                       stage); a bf16 store is faster through LDS like the 64-row tiles
+// The ranges are sized on the host from upper bounds; workgroups beyond the tiles that exist return.
+// A half without a tile of its own repeats its sibling's (same values to the same slots).
 template <int KVD, int AUX, bool SPLIT>
-__global__ __launch_bounds__(256, 2) void shared_mixed_kernel(SharedArgs a, int c0, int c1, int Hq, int Hkv, int C,
-                                                               int L, int k, float scale) {
-    __shared__ uint4 smem[lds_units<MIXED_KT>()];           // K/V stages, or the 33 KiB merge buffer
-    static_assert(sizeof(smem) >= sizeof(float) * 2 * 32 * OSTRIDE, "merge buffer of the 32-row streaming path");
-    const int first = a.tile_hdr[c0], end = a.tile_hdr[c1 + 1];
-    const int w = xcd_tile_index(end - first);
+__global__ __launch_bounds__(512, 2) void shared_all_kernel(SharedArgs a, int nb4, int nbL, int Hq, int Hkv, int C,
+                                                             int L, int k, float scale) {
+    constexpr int HALF = lds_units<64>();                   // 64 KiB of K/V stages, or a 33 KiB merge buffer
+    __shared__ uint4 smem[2 * HALF];
+    static_assert(sizeof(uint4) * HALF >= sizeof(float) * 2 * 32 * OSTRIDE, "merge buffer of the 32-row streaming path");
+    int bx = blockIdx.x;
+    if (bx < nb4) {
+        const int first = a.tile_hdr[4];
+        const int w = xcd_tile_index(bx, a.tile_hdr[5] - first);
+        if (w < 0) return;
+        lds_tile<2, 8, KVD, AUX, 64, 2, SPLIT>(a, a.tiles[2 * (first + w)], a.tiles[2 * (first + w) + 1], Hq, Hkv, C, L, k,
+                                               scale, smem, threadIdx.x);
+        return;
+    }
+    bx -= nb4;
+    const int half = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8), tid = threadIdx.x & 255;
+    uint4 *sm = smem + half * HALF;
+    constexpr int S0 = KVD == MOSKA_FP8_E4M3 ? 2 : 0;        // first class of the LDS-staged small tiles
+    const bool staged = bx < nbL;
+    if (!staged) bx -= nbL;
+    if (!staged && S0 == 0) return;
+    const int first = a.tile_hdr[staged ? S0 : 0], end = a.tile_hdr[staged ? 4 : S0], n = end - first;
+    const int w = xcd_tile_index(bx, (n + 1) >> 1);
     if (w < 0) return;
-    const int t = end - 1 - w;
+    const int i = 2 * w + half < n ? 2 * w + half : 2 * w;
+    const int t = end - 1 - i;                              // the list is walked from its end
     const int bkt = a.tiles[2 * t], row0 = a.tiles[2 * t + 1];
-    int cls = c0;
-    while (cls < c1 && t >= a.tile_hdr[cls + 1]) ++cls;
-    // Tiles of up to 32 rows: an fp8 store streams them (each wave its own keys, twice the bytes in
-    // flight of an fp8 LDS stage); a bf16 store is faster through LDS like the 64-row tiles.
-    if (KVD == MOSKA_FP8_E4M3 && cls == 0) stream_tile<1, KVD, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
-    else if (KVD == MOSKA_FP8_E4M3 && cls == 1) stream_tile<2, KVD, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)smem);
-    else if (cls <= 2) lds_tile<1, 4, KVD, AUX, MIXED_KT, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
-    else lds_tile<2, 4, KVD, AUX, MIXED_KT, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, smem);
+    if (staged) {
+        if (t >= a.tile_hdr[3]) lds_tile<2, 4, KVD, AUX, 64, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
+        else lds_tile<1, 4, KVD, AUX, 64, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
+    } else if constexpr (S0 > 0) {
+        if (t >= a.tile_hdr[1]) stream_tile<2, KVD, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)sm, tid);
+        else stream_tile<1, KVD, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)sm, tid);
+    }
 }
 
 }  // namespace mfma

@@ -10,12 +10,19 @@ namespace moska {
 
 constexpr int kWave = 64;
 
+// Override of a launch heuristic, for development builds only (-DMOSKA_TUNING: an integer from the named
+// environment variable); the library as shipped always gets the default.
+#ifdef MOSKA_TUNING
+int tuning_env(const char *name, int dflt);
+#else
+inline int tuning_env(const char *, int dflt) { return dflt; }
+#endif
+
 bool use_mfma_path(const moska_problem_t &p);
 
-// Work tiles of Shared KV Attention.  A bucket's rows are cut into tiles of one of five sizes;
-// tiles of one size class are served by one kernel launch.  A bucket of M rows becomes full tiles
-// of the largest class in the plan plus one remainder tile of the smallest class that holds it,
-// so every bucket's chunk is streamed as few times as possible.
+// Work tiles of Shared KV Attention.  A bucket's rows are cut into tiles of one of five sizes.
+// A bucket of M rows becomes full tiles of the largest class in the plan plus one remainder tile of
+// the smallest class that holds it, so every bucket's chunk is streamed as few times as possible.
 constexpr int kNumClasses = 5;
 __host__ __device__ constexpr int class_rows(int c) { return 16 << c; }   // 16, 32, 64, 128, 256
 struct SharedPlan {
@@ -23,23 +30,19 @@ struct SharedPlan {
 };
 SharedPlan shared_plan(const moska_problem_t &p);
 
-// Upper bound on the number of tiles of class c (host-known, sizes the launch grid): a remainder
-// tile of class c > cmin holds more than kClassRows[c-1] rows and a bucket has at most one; a bucket
-// holds at most one item per query token, i.e. B*G rows, so small batches have no large tiles at all.
-inline int64_t class_bound(const moska_problem_t &p, const SharedPlan &pl, int c) {
-    if (c < pl.cmin || c > pl.cmax) return 0;
+// Upper bound on the number of tiles of classes c_lo..c_hi (host-known, sizes the launch grid).  Pure
+// counting: a bucket has one remainder tile, there are at most min(items, buckets) non-empty buckets,
+// a remainder tile of class c > cmin holds more than class_rows(c-1) rows, and full tiles are of the
+// largest class.  It holds for any ids in [0,C), also repeated ones.
+inline int64_t tiles_bound(const moska_problem_t &p, const SharedPlan &pl, int c_lo, int c_hi) {
+    if (c_lo < pl.cmin) c_lo = pl.cmin;
+    if (c_hi > pl.cmax) c_hi = pl.cmax;
+    if (c_lo > c_hi) return 0;
     const int64_t items = (int64_t)p.B * p.Hkv * p.k, nb = (int64_t)p.Hkv * p.C;
     const int64_t rows = items * (p.Hq / p.Hkv);
-    if (c > pl.cmin && (int64_t)p.B * (p.Hq / p.Hkv) <= class_rows(c - 1)) return 0;
-    const int64_t nbe = items < nb ? items : nb;
-    int64_t rem = c == pl.cmin ? nbe : rows / (class_rows(c - 1) + 1);
-    if (rem > nbe) rem = nbe;
-    return c == pl.cmax ? rem + rows / class_rows(c) : rem;
-}
-inline int64_t max_tiles(const moska_problem_t &p, const SharedPlan &pl) {
-    int64_t t = 0;
-    for (int c = 0; c < kNumClasses; ++c) t += class_bound(p, pl, c);
-    return t;
+    int64_t rem = items < nb ? items : nb;
+    if (c_lo > pl.cmin && rows / (class_rows(c_lo - 1) + 1) < rem) rem = rows / (class_rows(c_lo - 1) + 1);
+    return c_hi == pl.cmax ? rem + rows / class_rows(pl.cmax) : rem;
 }
 
 // Unique KV Attention splits each request's context over this many workgroups when there are too

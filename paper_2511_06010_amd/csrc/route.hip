@@ -8,8 +8,11 @@
 // (the contraction index is permuted so that what a lane loads is what it feeds).  Scores leave
 // as order-preserving 64-bit keys in the workspace.
 //
-// Selection: one wave per (request, KV head) pulls its C keys into LDS and extracts the k best
-// with k rounds of a butterfly arg-max over (key descending, chunk id ascending).
+// Selection: one wave per (request, KV head) extracts the k best in k rounds of "largest key of the
+// wave, lowest chunk id among its holders".  Up to 1024 chunks the keys stay in registers (lane l holds
+// chunks l, l+64, ...) and the wave-wide maximum / minimum run on the vector ALU (DPP permutes, then
+// v_permlane16_swap / v_permlane32_swap); above that the keys sit in LDS and only a round's winner
+// rescans its chunks.
 //
 // Head sizes other than 64/128/256 take a vector-ALU scoring kernel (one chunk row per lane).
 #include "moska_internal.h"

@@ -122,29 +122,54 @@ def check_against_oracle(inp_cpu: Inputs, label: str = ""):
     return buf, st
 
 
-def sub_inputs(inp: Inputs, ids: torch.Tensor, b: int, h: int) -> tuple[Inputs, torch.Tensor]:
-    """The single-(query token, KV head) problem of (b,h): its k routed chunks gathered into a
-    compact store, its G query heads and the unique context it may see, as CPU tensors for the
-    oracle.  With several query tokens per request, b counts query tokens (request b // T, token
-    b % T) and the sub-problem is the single-token one with the context cut at the token."""
+def sub_inputs(inp: Inputs, ids: torch.Tensor, b: int, heads=None) -> tuple[Inputs, torch.Tensor]:
+    """The single-query-token problem of token b on KV heads `heads` (default: all of them): for
+    each head its k routed chunks gathered into a compact store (compact chunk j of head h is chunk
+    ids[b,h,j]), the query heads of those groups and the unique context the token may see, as CPU
+    tensors for the oracle.  With several query tokens per request, b counts query tokens (request
+    b // T, token b % T) and the context is cut at the token."""
     p = inp.prob
     G = p.G
+    hs = list(range(p.Hkv)) if heads is None else list(heads)
+    dev = inp.Ks.device
+    hv = torch.tensor(hs, device=dev)
     req, t = divmod(b, p.T)
-    sel = ids[b, h].long().to(inp.Ks.device)
-    sp = p.with_(B=1, T=1, Hq=G, Hkv=1, C=p.k, name=p.name + f"-sub{b}.{h}")
-    cpu = lambda t: t.contiguous().cpu()
+    sel = ids[b, hs].long().to(dev).t().contiguous()              # [k, nh]: chunk of (slot j, head)
+    qrows = torch.cat([torch.arange(h * G, (h + 1) * G) for h in hs]).to(dev)
+    sp = p.with_(B=1, T=1, Hq=G * len(hs), Hkv=len(hs), C=p.k, name=p.name + f"-sub{b}")
+    cpu = lambda x: x.contiguous().cpu()
     sub = Inputs(
         sp,
-        Q=cpu(inp.Q[b:b + 1, h * G:(h + 1) * G]),
-        E=cpu(inp.E[h:h + 1, sel]),
-        Ks=cpu(inp.Ks[sel, h:h + 1]),
-        Vs=cpu(inp.Vs[sel, h:h + 1]),
-        scale_k=None if inp.scale_k is None else cpu(inp.scale_k[sel, h:h + 1]),
-        scale_v=None if inp.scale_v is None else cpu(inp.scale_v[sel, h:h + 1]),
-        Ku=cpu(inp.Ku[req:req + 1, h:h + 1]),
-        Vu=cpu(inp.Vu[req:req + 1, h:h + 1]),
+        Q=cpu(inp.Q[b:b + 1, qrows]),
+        E=cpu(inp.E[hv[None, :], sel].permute(1, 0, 2)),          # [nh, k, D]
+        Ks=cpu(inp.Ks[sel, hv[None, :]]),                         # [k, nh, L, D]
+        Vs=cpu(inp.Vs[sel, hv[None, :]]),
+        scale_k=None if inp.scale_k is None else cpu(inp.scale_k[sel, hv[None, :]]),
+        scale_v=None if inp.scale_v is None else cpu(inp.scale_v[sel, hv[None, :]]),
+        Ku=cpu(inp.Ku[req:req + 1, hv]),
+        Vu=cpu(inp.Vu[req:req + 1, hv]),
         unique_len=cpu((inp.unique_len[req:req + 1] - (p.T - 1 - t)).clamp_min(0)),
         cstar=cpu(inp.cstar[req:req + 1]),
     )
-    sub_ids = torch.arange(p.k, dtype=torch.int32).reshape(1, 1, p.k)
+    sub_ids = torch.arange(p.k, dtype=torch.int32).reshape(1, 1, p.k).repeat(1, len(hs), 1).contiguous()
     return sub, sub_ids
+
+
+def stratified_tokens(p: Problem, off: torch.Tensor, items: torch.Tensor, n: int, seed: int) -> list[int]:
+    """n query tokens chosen by bucket popularity: the first and last item of the hottest and of the
+    coldest non-empty bucket, one item of the buckets at the size quartiles, then seeded random tokens."""
+    sizes = off[1:] - off[:-1]
+    nz = torch.nonzero(sizes > 0).flatten()
+    order = nz[torch.argsort(sizes[nz], stable=True)]
+    picks = [order[-1], order[0]] + [order[int(q * (len(order) - 1))] for q in (0.25, 0.5, 0.75)]
+    toks = []
+    for bk in picks:
+        for item in (items[off[bk]], items[off[bk + 1] - 1]):
+            toks.append(int(item) // p.k)
+    g = torch.Generator().manual_seed(seed)
+    out = list(dict.fromkeys(toks))
+    while len(out) < min(n, p.Bq):
+        t = int(torch.randint(0, p.Bq, (1,), generator=g))
+        if t not in out:
+            out.append(t)
+    return out

@@ -362,6 +362,25 @@ def test_quantize_fp8_scales_and_roundtrip():
     assert ((back - X.float()).abs() <= amax[:, :, None, None] * 2.0 ** -4 + 1e-12).all()   # half an ulp at the top binade
 
 
+def test_quantize_fp8_all_zero_block_gets_the_floor_scale():
+    # a block of zeros (positive and negative) has amax 0: its scale is the floor 1e-30 in f32, every
+    # byte encodes a zero (the sign bit may survive, the magnitude bits may not), and the block
+    # decodes to exact zeros; its neighbour is quantised as usual
+    p = small(q_dtype="bf16", kv_dtype="fp8", D=16, C=2, L=24, Hkv=1, Hq=1)
+    g = torch.Generator().manual_seed(22)
+    X = torch.randn(p.C, p.Hkv, p.L, p.D, generator=g).to(torch.bfloat16)
+    X[0] = 0.0
+    X[0, 0, 3, 5] = -0.0
+    X8, sc = oracle.quantize_fp8(p, X)
+    assert sc[0, 0].item() == torch.tensor(1e-30, dtype=torch.float32).item()
+    assert ((X8[0].view(torch.uint8) & 0x7F) == 0).all()
+    assert (oracle.widen(X8[0]) * float(sc[0, 0]) == 0).all()
+    amax = X[1].float().abs().max()
+    assert sc[1, 0].item() == (amax / 448.0).item()
+    want = (X[1].float() / sc[1, 0]).clamp(-448, 448).to(torch.float8_e4m3fn)
+    assert torch.equal(X8[1].view(torch.uint8), want.view(torch.uint8))
+
+
 @pytest.mark.parametrize("dt,kv", [("f32", "f32"), ("bf16", "bf16"), ("bf16", "fp8")])
 def test_chunk_embeddings_are_the_mean_key(dt, kv):
     p = small(q_dtype=dt, kv_dtype=kv, C=4, L=37, D=32)
