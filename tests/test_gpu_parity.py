@@ -7,7 +7,7 @@ import torch
 import oracle
 import paper_2511_06010_amd as moska
 from moska_inputs import Problem, config, generate
-from parity import (assert_lse_close, assert_vectors_close, check_against_oracle, check_route, gpu_pipeline,
+from parity import (assert_lse_close, assert_vectors_close, check_against_oracle, check_route, gpu_pipeline, stratified_tokens,
                     sub_inputs, tol_key)
 
 pytestmark = pytest.mark.gpu
