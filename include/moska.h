@@ -62,7 +62,8 @@ typedef enum {
     MOSKA_ERR_INVALID_ARG = -1,          /* null pointer, non-positive size, k > C, Hq % Hkv != 0 ... */
     MOSKA_ERR_UNSUPPORTED = -2,          /* dtype combination or size outside the built kernels */
     MOSKA_ERR_WORKSPACE_TOO_SMALL = -3,
-    MOSKA_ERR_HIP = -4                   /* a HIP runtime call (launch, attribute) failed */
+    MOSKA_ERR_HIP = -4,                  /* a HIP runtime call (launch, attribute) failed */
+    MOSKA_ERR_SCRATCH_LIMIT = -5         /* moska_decode_step_static: workspace need exceeds MOSKA_STATIC_SCRATCH_BYTES */
 } moska_status_t;
 
 typedef struct {
@@ -137,6 +138,24 @@ int moska_decode_step(const moska_problem_t *p, const void *Q, const void *E,
                       int32_t *ids, int32_t *bucket_off, int32_t *bucket_items,
                       float *part_O, float *part_LSE, void *O, float *LSE,
                       void *ws, size_t ws_bytes, void *stream);
+
+/* moska_decode_step for callers that cannot allocate a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The workspace is a static array of
+ * MOSKA_STATIC_SCRATCH_BYTES in the library's own device memory (each GPU the library runs on
+ * holds one until the process ends); the call allocates and frees nothing.  Inputs, outputs and
+ * results are those of moska_decode_step (the same kernels run).
+ *   - A problem whose moska_workspace_bytes exceeds MOSKA_STATIC_SCRATCH_BYTES is rejected with
+ *     MOSKA_ERR_SCRATCH_LIMIT before anything is launched.
+ *   - The array's device address is looked up on the first call on each GPU; make that call
+ *     outside stream capture.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two host threads) race.  Nothing in it has to be cleared between calls. */
+#define MOSKA_STATIC_SCRATCH_BYTES (16u << 20)
+int moska_decode_step_static(const moska_problem_t *p, const void *Q, const void *E,
+                             const void *Ks, const void *Vs, const float *scale_k, const float *scale_v,
+                             const void *Ku, const void *Vu, const int32_t *unique_len,
+                             int32_t *ids, int32_t *bucket_off, int32_t *bucket_items,
+                             float *part_O, float *part_LSE, void *O, float *LSE, void *stream);
 
 /* Offline construction of the shared store (Sec. III-A: pre-computed shared KV caches;
  * Sec. III-B: precomputed chunk embeddings).  Not part of the decode step.

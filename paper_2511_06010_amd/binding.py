@@ -20,7 +20,7 @@ _DT = {"f32": F32, "bf16": BF16, "fp8": FP8_E4M3}
 _TORCH = {F32: torch.float32, BF16: torch.bfloat16, FP8_E4M3: torch.float8_e4m3fn}
 
 EXPORTS = ("moska_workspace_bytes", "moska_route", "moska_bucket", "moska_shared_attn", "moska_unique_attn",
-           "moska_merge", "moska_decode_step", "moska_chunk_embeddings", "moska_quantize_shared", "moska_status_string")
+           "moska_merge", "moska_decode_step", "moska_decode_step_static", "moska_chunk_embeddings", "moska_quantize_shared", "moska_status_string")
 
 
 class MoskaError(RuntimeError):
@@ -170,6 +170,28 @@ def decode_step(p, Q, E, Ks, Vs, scale_k, scale_v, Ku, Vu, unique_len, ids, buck
         _dev(O, qd, (cp.Bq, cp.Hq, cp.D), "O"), _dev(LSE, torch.float32, (cp.Bq, cp.Hq), "LSE"),
         _dev(ws, torch.uint8, name="ws"), ctypes.c_size_t(0 if ws is None else ws.numel()), _stream())
     _check(rc, "moska_decode_step")
+
+
+STATIC_SCRATCH_BYTES = 16 << 20        # MOSKA_STATIC_SCRATCH_BYTES
+
+
+def decode_step_static(p, Q, E, Ks, Vs, scale_k, scale_v, Ku, Vu, unique_len, ids, bucket_off, bucket_items,
+                       part_O, part_LSE, O, LSE):
+    cp = problem_t(p)
+    qd, kd = _TORCH[cp.q_dtype], _TORCH[cp.shared_kv_dtype]
+    rc = load_library().moska_decode_step_static(
+        ctypes.byref(cp), _dev(Q, qd, (cp.Bq, cp.Hq, cp.D), "Q"), _dev(E, qd, (cp.Hkv, cp.C, cp.D), "E"),
+        _dev(Ks, kd, (cp.C, cp.Hkv, cp.L, cp.D), "Ks"), _dev(Vs, kd, (cp.C, cp.Hkv, cp.L, cp.D), "Vs"),
+        _dev(scale_k, torch.float32, (cp.C, cp.Hkv), "scale_k"), _dev(scale_v, torch.float32, (cp.C, cp.Hkv), "scale_v"),
+        _dev(Ku, qd, (cp.B, cp.Hkv, cp.U_max, cp.D), "Ku"), _dev(Vu, qd, (cp.B, cp.Hkv, cp.U_max, cp.D), "Vu"),
+        _dev(unique_len, torch.int32, (cp.B,), "unique_len"),
+        _dev(ids, torch.int32, (cp.Bq, cp.Hkv, cp.k), "ids"),
+        _dev(bucket_off, torch.int32, (cp.Hkv * cp.C + 1,), "bucket_off"),
+        _dev(bucket_items, torch.int32, (cp.Bq * cp.Hkv * cp.k,), "bucket_items"),
+        _dev(part_O, torch.float32, (cp.Bq, cp.Hq, cp.k + 1, cp.D), "part_O"),
+        _dev(part_LSE, torch.float32, (cp.Bq, cp.Hq, cp.k + 1), "part_LSE"),
+        _dev(O, qd, (cp.Bq, cp.Hq, cp.D), "O"), _dev(LSE, torch.float32, (cp.Bq, cp.Hq), "LSE"), _stream())
+    _check(rc, "moska_decode_step_static")
 
 
 def chunk_embeddings(p, Ks, scale_k, E):

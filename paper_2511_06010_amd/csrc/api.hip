@@ -1,6 +1,7 @@
 // C entry points: host-side validation, workspace carving and kernel dispatch.
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "moska_internal.h"
 
@@ -116,6 +117,28 @@ static int check_problem(const moska_problem_t *p) {
     return MOSKA_OK;
 }
 
+// Workspace of moska_decode_step_static: one array per GPU, in the library's own device memory for
+// as long as the process lives.  `scratch` is a host-side stand-in for the symbol, not a device
+// address; its address on the current device is looked up once per device and kept in scratch_ptr.
+constexpr size_t kScratchBytes = (size_t)MOSKA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+static void *scratch_ptr[kMaxDevices];
+static std::mutex scratch_mutex;
+
+static int scratch_of_current_device(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MOSKA_ERR_HIP;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MOSKA_ERR_HIP;
+        scratch_ptr[dev] = ptr;
+    }
+    *out = scratch_ptr[dev];
+    return MOSKA_OK;
+}
+
 }  // namespace moska
 
 using namespace moska;
@@ -129,6 +152,7 @@ const char *moska_status_string(int status) {
     case MOSKA_ERR_UNSUPPORTED: return "unsupported dtype or size";
     case MOSKA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
     case MOSKA_ERR_HIP: return "HIP runtime error";
+    case MOSKA_ERR_SCRATCH_LIMIT: return "problem needs more workspace than the static scratch buffer holds";
     default: return "unknown status";
     }
 }
@@ -228,6 +252,19 @@ int moska_decode_step(const moska_problem_t *p, const void *Q, const void *E, co
         return rc;
     if (int rc = moska_unique_attn(p, Q, Ku, Vu, unique_len, part_O, part_LSE, ws, ws_bytes, stream)) return rc;
     return moska_merge(p, part_O, part_LSE, O, LSE, stream);
+}
+
+int moska_decode_step_static(const moska_problem_t *p, const void *Q, const void *E, const void *Ks, const void *Vs,
+                             const float *scale_k, const float *scale_v, const void *Ku, const void *Vu,
+                             const int32_t *unique_len, int32_t *ids, int32_t *bucket_off, int32_t *bucket_items,
+                             float *part_O, float *part_LSE, void *O, float *LSE, void *stream) {
+    if (int rc = check_problem(p)) return rc;
+    if (carve_workspace(*p, nullptr).bytes > kScratchBytes) return MOSKA_ERR_SCRATCH_LIMIT;
+    void *ws = nullptr;
+    if (int rc = scratch_of_current_device(&ws)) return rc;
+    // nothing in the workspace has to start at zero: every region is written before it is read
+    return moska_decode_step(p, Q, E, Ks, Vs, scale_k, scale_v, Ku, Vu, unique_len, ids, bucket_off, bucket_items,
+                             part_O, part_LSE, O, LSE, ws, kScratchBytes, stream);
 }
 
 int moska_chunk_embeddings(const moska_problem_t *p, const void *Ks, const float *scale_k, void *E, void *stream) {
