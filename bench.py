@@ -119,7 +119,7 @@ def paper_sweep(steps, warmup):
         torch.cuda.empty_cache()
 
 
-def reuse_sweep(steps, warmup):
+def reuse_sweep(steps, warmup, stores=("bf16", "fp8")):
     """Shared attention against query rows per bucket at the chunk shape of configs 2-4 (L = 4096,
     D = 128, 8 KV heads, G = 4): 16 chunks, every request attends all of them (k = C), so each of the
     128 buckets holds exactly 4*B rows.  Shows where the path leaves the HBM roofline for the MFMA
@@ -127,7 +127,7 @@ def reuse_sweep(steps, warmup):
     import torch
     import paper_2511_06010_amd as moska
     from moska_inputs import Problem, generate
-    for kv in ("bf16", "fp8"):
+    for kv in stores:
         for B in (4, 8, 16, 32, 64, 128, 256, 512, 1024):
             p = Problem(B=B, Hq=32, Hkv=8, D=128, C=16, L=4096, k=16, U=64, kv_dtype=kv, name=f"reuse-{kv}-m{4 * B}")
             inp = generate(p, seed=20251106, device="cuda")
@@ -262,6 +262,7 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=0, help="requests in the oracle's sample (0 = auto)")
     ap.add_argument("--reuse-sweep", action="store_true",
                     help="shared attention against rows per bucket (16..4096) instead of the decode step")
+    ap.add_argument("--sweep-store", choices=["bf16", "fp8"], help="restrict --reuse-sweep to one store dtype")
     ap.add_argument("--paper-sweep", action="store_true",
                     help="instead of the benchmark line: utilisation against batch size at the paper's operating point")
     ap.add_argument("--calibrate", action="store_true", help="run the 1 GiB calibration copy and exit")
@@ -282,7 +283,7 @@ def main():
         calibrate()
         return
     if args.reuse_sweep:
-        reuse_sweep(args.steps, args.warmup)
+        reuse_sweep(args.steps, args.warmup, (args.sweep_store,) if args.sweep_store else ("bf16", "fp8"))
         return
     if args.paper_sweep:
         paper_sweep(args.steps, args.warmup)

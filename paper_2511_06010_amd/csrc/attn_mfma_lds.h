@@ -236,48 +236,320 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
     store_rows<NR, !SPLIT>(st, q, orow, vmul, SPLIT ? a.split_O : a.part_O, SPLIT ? a.split_LSE : a.part_LSE);
 }
 
+// ---- fp8 store: scores on the fp8 matrix cores --------------------------------------------------
+//
+// v_mfma_scale_f32_16x16x128_f8f6f4 contracts all 128 head dims of 16 keys x 16 query rows in one
+// instruction, at twice the rate of the bf16 MFMA, from e4m3 operands with a power-of-two scale
+// per row.  The keys of an fp8 store are its A operand as they are: they stay fp8 in LDS (half the
+// stage bytes and half the LDS read traffic of the bf16 stage, no widening).  The query row has no
+// fp8 twin, so it is carried as a pair hi + lo of e4m3 values (hi = the row rounded to e4m3 after
+// scaling its largest element into [128, 256), lo = the rounding error, again in e4m3): together
+// 8 significant bits, the precision of the bf16 query itself, for two MFMAs at the doubled rate --
+// the cost of the bf16 contraction.  The logit scale, the keys' dequantisation factor and log2(e)
+// are folded into the query before the split, and the running reference point m of the softmax row
+// enters as the accumulator's initial value, so the MFMA hands the softmax s*log2(e) - m directly
+// and the per-score scale-and-subtract disappears from the vector ALU.
+// Operand layout (measured): lane (q,x) holds 32 bytes of row x; the instruction pairs A and B
+// bytes position by position, so any 32 dims may sit there as long as both operands agree; the
+// block scales of a row are taken from the scale registers of the row's four lanes, which hold
+// one common value here.
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+
+__device__ __forceinline__ f32x4 mfma_f8(const i32x8 &a, const i32x8 &b, f32x4 c, int scale_b) {
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0, 0, 0, 0x7F7F7F7F, 0, scale_b);
+}
+
+struct QueryF8 {
+    i32x8 hi, lo;       // dims 32q .. 32q+31 of the scaled row, and the rounding error of hi
+    int scale;          // e8m0 exponent byte (replicated) that undoes the row's scaling
+};
+
+// Row at element offset qoff of Q (bf16), times c, as an fp8 pair; a padding row (valid = false) is zero.
+__device__ __forceinline__ void load_q_f8(QueryF8 &qf, const void *Q, int64_t qoff, bool valid, float c, int q) {
+    float xv[32];
+    float amax = 0.f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        uint4 v = {0u, 0u, 0u, 0u};
+        if (valid) v = *(const uint4 *)((const uint16_t *)Q + qoff + 32 * q + 8 * u);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            xv[8 * u + 2 * i] = bf16_bits_to_f32(w[i] & 0xFFFFu) * c;
+            xv[8 * u + 2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u) * c;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 32; ++i) amax = fmaxf(amax, fabsf(xv[i]));
+    amax = row_lanes_max(amax);                             // over the row's 128 dims
+    int e = amax > 0.f ? __builtin_amdgcn_frexp_expf(amax) : 0;   // amax = f * 2^e, f in [0.5, 1)
+    int sh = 8 - e;                                         // largest element lands in [128, 256)
+    sh = sh > 100 ? 100 : sh < -100 ? -100 : sh;
+    const int sb = 127 - sh;                                // the MFMA multiplies the row by 2^(sb - 127)
+    qf.scale = sb | (sb << 8) | (sb << 16) | (sb << 24);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float y[4], r[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) y[j] = __builtin_ldexpf(xv[4 * i + j], sh);
+        int h = 0;
+        h = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], h, false);
+        h = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], h, true);
+        const f32x2 b0 = __builtin_amdgcn_cvt_pk_f32_fp8(h, false), b1 = __builtin_amdgcn_cvt_pk_f32_fp8(h, true);
+        r[0] = y[0] - b0[0]; r[1] = y[1] - b0[1]; r[2] = y[2] - b1[0]; r[3] = y[3] - b1[1];
+        int l = 0;
+        l = __builtin_amdgcn_cvt_pk_fp8_f32(r[0], r[1], l, false);
+        l = __builtin_amdgcn_cvt_pk_fp8_f32(r[2], r[3], l, true);
+        qf.hi[i] = h;
+        qf.lo[i] = l;
+    }
+}
+
+// t = s*log2(e) - m of one 32-key sub-tile: the key operands (fp8, 16-byte units of a 128-byte row
+// XOR-swizzled by key & 7) from LDS, the accumulators starting at -m of the lane's row.
+template <int NR>
+__device__ __forceinline__ void qk_from_lds_f8(f32x4 (&t)[NR][2], const QueryF8 (&qf)[NR], const f32x4 (&negm)[NR],
+                                               const uint4 *lk, int q, int x) {
+#pragma unroll
+    for (int kblk = 0; kblk < 2; ++kblk) {
+        const int row = 16 * kblk + x;
+        const uint4 u0 = lk[row * 8 + ((2 * q) ^ (row & 7))], u1 = lk[row * 8 + ((2 * q + 1) ^ (row & 7))];
+        const i32x8 kf = {(int)u0.x, (int)u0.y, (int)u0.z, (int)u0.w, (int)u1.x, (int)u1.y, (int)u1.z, (int)u1.w};
+#pragma unroll
+        for (int rb = 0; rb < NR; ++rb) {
+            const f32x4 acc = mfma_f8(kf, qf[rb].hi, negm[rb], qf[rb].scale);
+            t[rb][kblk] = mfma_f8(kf, qf[rb].lo, acc, qf[rb].scale);
+        }
+    }
+}
+
+// Online softmax on scores that arrive with the row's reference point already subtracted (log2
+// domain).  The reference moves only when a tile's maximum exceeds it by more than kLazy -- and at
+// the row's first tile (`first`, wave-uniform), where it moves onto the tile's maximum from its
+// starting value 0; only then are the scores corrected by the move.
+// negm: -m of the lane's row in all four components, the accumulator start of the next scores.
+template <int NR, bool TAIL>
+__device__ __forceinline__ void softmax_presub(WaveState<NR> &st, f32x4 (&negm)[NR], const f32x4 (&t)[NR][2],
+                                               uint32_t (&pf)[NR][4], int key0, int nkeys, int q, bool first) {
+    float v[NR][8], mx[NR];
+    bool over = first;
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) {
+#pragma unroll
+        for (int kblk = 0; kblk < 2; ++kblk)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float z = t[rb][kblk][r];
+                if (TAIL && key0 + 16 * kblk + 4 * q + r >= nkeys) z = -INFINITY;   // rows past the end read as 0
+                v[rb][4 * kblk + r] = z;
+            }
+        const float *w = v[rb];
+        mx[rb] = fmaxf(fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])), fmaxf(fmaxf(w[4], w[5]), fmaxf(w[6], w[7])));
+        over |= mx[rb] > kLazy;
+    }
+    if (__any(over)) {
+        float alpha[NR];
+#pragma unroll
+        for (int rb = 0; rb < NR; ++rb) {
+            const float rmx = row_lanes_max(mx[rb]);
+            const float delta = (first || rmx > kLazy) ? rmx : 0.f;     // finite: a tile holds a key of every row
+            alpha[rb] = __builtin_amdgcn_exp2f(-delta);
+            st.m[rb] += delta;
+            negm[rb] = f32x4{-st.m[rb], -st.m[rb], -st.m[rb], -st.m[rb]};
+            st.l[rb] *= alpha[rb];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[rb][i] -= delta;
+        }
+#pragma unroll
+        for (int rb = 0; rb < NR; ++rb)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) st.o[rb][e][r] *= alpha[rb];
+    }
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[rb][i] = __builtin_amdgcn_exp2f(v[rb][i]);
+        pf[rb][0] = pack_bf16(v[rb][0], v[rb][1]);
+        pf[rb][1] = pack_bf16(v[rb][2], v[rb][3]);
+        pf[rb][2] = pack_bf16(v[rb][4], v[rb][5]);
+        pf[rb][3] = pack_bf16(v[rb][6], v[rb][7]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) st.l[rb] = dot2_ones(pf[rb][i], st.l[rb]);
+    }
+}
+
+// LDS of the fp8 tile, in uint4 units: two buffers of 64-key stages, keys as fp8 (8 units a key), values as bf16 (16)
+constexpr int lds_units_f8() { return 2 * 64 * 8 + 2 * 64 * 16; }
+
+// Tile (bkt, row0) of an fp8 store on the LDS-staged path with fp8 scores: 16*NR*NWV rows, by the
+// NWV*64 threads tid = 0 .. NWV*64-1 that share smem (lds_units_f8() uint4); stages of 64 keys, PD
+// (1 or 2) stages of global loads in flight.  One workgroup barrier per stage plus one, as lds_tile.
+template <int NR, int NWV, int AUX, int PD, bool SPLIT>
+__device__ __forceinline__ void lds_tile_f8(const SharedArgs &a, int bkt, int row0, int Hq, int Hkv, int C, int Lchunk,
+                                            int k, float scale, uint4 *smem, int tid) {
+    static_assert(PD == 1 || PD == 2, "stages in flight");
+    constexpr int KVD = MOSKA_FP8_E4M3, KT = 64, T = NWV * 64;
+    constexpr int KU = KT * 8, VU = KT * 16;                // uint4 units of a K stage and of a V stage
+    uint4 *ldsK = smem, *ldsV = smem + 2 * KU;
+    const int h = bkt / C, c = bkt - h * C, G = Hq / Hkv;
+    const int lane = tid & 63, q = lane >> 4, x = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    int first_key, L;
+    key_slice(Lchunk, a.nsplit, blockIdx.y, KT, first_key, L);
+    const int64_t base = (((int64_t)c * Hkv + h) * Lchunk + first_key) * row_bytes<KVD>();
+    const __amdgpu_buffer_rsrc_t rk = key_set_rsrc((const char *)a.Ks + base, (uint32_t)L * row_bytes<KVD>());
+    const __amdgpu_buffer_rsrc_t rv = key_set_rsrc((const char *)a.Vs + base, (uint32_t)L * row_bytes<KVD>());
+    const int nst = (L + KT - 1) / KT;
+    StageRegs<KVD, T, KT> regs[PD];
+    stage_fetch<KVD, T, KT, AUX>(regs[0], rk, rv, 0, tid);
+
+    const float kmul = a.scale_k[c * Hkv + h], vmul = a.scale_v[c * Hkv + h];
+    const int beg = a.off[bkt], rows = (a.off[bkt + 1] - beg) * G;
+    QueryF8 qf[NR];
+    int64_t orow[NR];
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) {
+        const int rr = row0 + (wave * NR + rb) * 16 + x;
+        const bool valid = rr < rows;
+        int64_t qoff = 0;
+        orow[rb] = -1;
+        if (valid) {
+            const int item = a.items[beg + rr / G], g = rr % G;
+            const int b = item / k, j = item - b * k;
+            const int64_t bh = (int64_t)b * Hq + h * G + g;
+            qoff = bh * HD;
+            orow[rb] = shared_out_row(a, bh, j, k, blockIdx.y);
+        }
+        load_q_f8(qf[rb], a.Q, qoff, valid, scale * kmul * kLog2e, q);
+    }
+
+    WaveState<NR> st;
+    f32x4 negm[NR];
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) {
+        st.m[rb] = 0.f;                                     // moved onto the first tile's maximum by softmax_presub
+        negm[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        st.l[rb] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st.o[rb][e] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const bool has_rows = row0 + wave * (16 * NR) < rows;
+    auto consume = [&](int t, int cur) {
+        if (!has_rows) return;
+#pragma unroll
+        for (int sub = 0; sub < KT / 32; ++sub) {
+            f32x4 s[NR][2];
+            uint32_t pf[NR][4];
+            const int key0 = KT * t + 32 * sub;
+            qk_from_lds_f8<NR>(s, qf, negm, ldsK + cur * KU + sub * 256, q, x);
+            if (key0 + 32 > L) softmax_presub<NR, true>(st, negm, s, pf, key0, L, q, key0 == 0);
+            else softmax_presub<NR, false>(st, negm, s, pf, key0, L, q, key0 == 0);
+            pv_from_lds<NR>(st, ldsV + cur * VU + sub * 512, pf, lane);
+        }
+    };
+    auto store = [&](const StageRegs<KVD, T, KT> &r, int buf) {
+        uint4 *lk = ldsK + buf * KU, *lv = ldsV + buf * VU;
+#pragma unroll
+        for (int i = 0; i < StageRegs<KVD, T, KT>::N; ++i) {
+            const int g = tid + i * T, row = g >> 3, u = g & 7;
+            lk[row * 8 + (u ^ (row & 7))] = r.k[i];         // keys stay fp8
+            uint4 lo, hi;
+            fp8x16_to_bf16(r.v[i], lo, hi);                 // values are widened for the bf16 P V product
+            const int vb = (u ^ (row & 7)) * 2;
+            lv[row * 16 + vb] = lo;
+            lv[row * 16 + vb + 1] = hi;
+        }
+    };
+    store(regs[0], 0);
+    if constexpr (PD == 1) {
+        __syncthreads();
+        for (int t = 0; t < nst; ++t) {
+            const int cur = t & 1;
+            stage_fetch<KVD, T, KT, AUX>(regs[0], rk, rv, t + 1, tid);
+            consume(t, cur);
+            store(regs[0], cur ^ 1);
+            __syncthreads();
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < PD; ++j) stage_fetch<KVD, T, KT, AUX>(regs[(1 + j) % PD], rk, rv, 1 + j, tid);
+        __syncthreads();
+        for (int t0 = 0; t0 < nst; t0 += PD) {
+#pragma unroll
+            for (int u = 0; u < PD; ++u) {
+                const int t = t0 + u;
+                if (t < nst) {
+                    consume(t, u & 1);
+                    StageRegs<KVD, T, KT> &nx = regs[(u + 1) % PD];
+                    store(nx, (u + 1) & 1);
+                    stage_fetch<KVD, T, KT, AUX>(nx, rk, rv, t + 1 + PD, tid);
+                    __syncthreads();
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int rb = 0; rb < NR; ++rb) st.l[rb] = row_lanes_sum(st.l[rb]);
+    store_rows<NR, !SPLIT>(st, q, orow, vmul, SPLIT ? a.split_O : a.part_O, SPLIT ? a.split_LSE : a.part_LSE);
+}
+
 // The whole tile list in ONE launch of 512-thread workgroups, so that no size class pays a kernel's
-// fill and drain of its own and the long 256-row tiles run beside the streaming ones.  Three ranges
-// of workgroups, each a multiple of 8 long, largest tiles first:
-//   [0, nb4)            one 256-row tile per workgroup (8 waves x 32 rows)
-//   [nb4, nb4 + nbL)    two LDS-staged tiles of up to 128 rows per workgroup, one per half (4 waves
+// fill and drain of its own and the long 256-row tiles run beside the streaming ones.  Three kinds
+// of work item:
+//   256-row tile        one per workgroup (8 waves x 32 rows)
+//   staged pair         two LDS-staged tiles of up to 128 rows per workgroup, one per half (4 waves
 //                       each, with its own half of the LDS); both halves stream chunks of the same
 //                       length, so they execute the same number of workgroup barriers
-//   the rest            (fp8 store) two streaming tiles of up to 32 rows, one per half: an fp8 store
+//   streaming pair      (fp8 store) two streaming tiles of up to 32 rows, one per half: an fp8 store
 //                       streams them (each wave its own keys, twice the bytes in flight of an fp8 LDS
 //                       stage); a bf16 store is faster through LDS like the 64-row tiles
-// The ranges are sized on the host from upper bounds; workgroups beyond the tiles that exist return.
+// The grid is sized on the host from upper bounds; workgroups beyond the items that exist return.
 // A half without a tile of its own repeats its sibling's (same values to the same slots).
 template <int KVD, int AUX, bool SPLIT>
-__global__ __launch_bounds__(512, 2) void shared_all_kernel(SharedArgs a, int nb4, int nbL, int Hq, int Hkv, int C,
+__global__ __launch_bounds__(512, 2) void shared_all_kernel(SharedArgs a, int Hq, int Hkv, int C,
                                                              int L, int k, float scale) {
     constexpr int HALF = lds_units<64>();                   // 64 KiB of K/V stages, or a 33 KiB merge buffer
     __shared__ uint4 smem[2 * HALF];
     static_assert(sizeof(uint4) * HALF >= sizeof(float) * 2 * 32 * OSTRIDE, "merge buffer of the 32-row streaming path");
-    int bx = blockIdx.x;
-    if (bx < nb4) {
-        const int first = a.tile_hdr[4];
-        const int w = xcd_tile_index(bx, a.tile_hdr[5] - first);
-        if (w < 0) return;
-        lds_tile<2, 8, KVD, AUX, 64, 2, SPLIT>(a, a.tiles[2 * (first + w)], a.tiles[2 * (first + w) + 1], Hq, Hkv, C, L, k,
-                                               scale, smem, threadIdx.x);
+    constexpr int S0 = KVD == MOSKA_FP8_E4M3 ? 2 : 0;        // first class of the LDS-staged small tiles
+    // work items: 256-row tiles, pairs of LDS-staged small tiles, pairs of streaming tiles; each XCD
+    // (workgroups are dealt to the 8 XCDs round-robin) takes a contiguous share of each list, so that
+    // the tiles of one bucket, which re-read the same chunk, share an L2
+    const int n4 = a.tile_hdr[5] - a.tile_hdr[4], nL = a.tile_hdr[4] - a.tile_hdr[S0], nS = a.tile_hdr[S0] - a.tile_hdr[0];
+    const int p4 = (n4 + 7) >> 3, pL = (((nL + 1) >> 1) + 7) >> 3, pS = (((nS + 1) >> 1) + 7) >> 3;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, per = p4 + pL + pS;
+    if (slot >= per) return;
+    // slot -> (kind, index inside the XCD's share): the long 256-row tiles first.  (Spreading them
+    // evenly among the others, or putting them last, measured the same to within 3 %.)
+    if (slot < p4) {
+        const int w = xcd * p4 + slot;
+        if (w >= n4) return;
+        const int t = a.tile_hdr[4] + w;
+        if constexpr (KVD == MOSKA_FP8_E4M3)
+            lds_tile_f8<2, 8, AUX, 2, SPLIT>(a, a.tiles[2 * t], a.tiles[2 * t + 1], Hq, Hkv, C, L, k, scale, smem, threadIdx.x);
+        else
+            lds_tile<2, 8, KVD, AUX, 64, 2, SPLIT>(a, a.tiles[2 * t], a.tiles[2 * t + 1], Hq, Hkv, C, L, k, scale, smem,
+                                                   threadIdx.x);
         return;
     }
-    bx -= nb4;
+    int r = slot - p4;                                      // index among the XCD's pairs: staged ones first
     const int half = __builtin_amdgcn_readfirstlane(threadIdx.x >> 8), tid = threadIdx.x & 255;
     uint4 *sm = smem + half * HALF;
-    constexpr int S0 = KVD == MOSKA_FP8_E4M3 ? 2 : 0;        // first class of the LDS-staged small tiles
-    const bool staged = bx < nbL;
-    if (!staged) bx -= nbL;
-    if (!staged && S0 == 0) return;
-    const int first = a.tile_hdr[staged ? S0 : 0], end = a.tile_hdr[staged ? 4 : S0], n = end - first;
-    const int w = xcd_tile_index(bx, (n + 1) >> 1);
-    if (w < 0) return;
+    const bool staged = r < pL;
+    if (!staged) r -= pL;
+    const int n = staged ? nL : nS, w = xcd * (staged ? pL : pS) + r;
+    if (2 * w >= n) return;
     const int i = 2 * w + half < n ? 2 * w + half : 2 * w;
-    const int t = end - 1 - i;                              // the list is walked from its end
+    const int t = a.tile_hdr[staged ? 4 : S0] - 1 - i;      // each list is walked from its end: largest tiles first
     const int bkt = a.tiles[2 * t], row0 = a.tiles[2 * t + 1];
     if (staged) {
-        if (t >= a.tile_hdr[3]) lds_tile<2, 4, KVD, AUX, 64, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
+        if constexpr (KVD == MOSKA_FP8_E4M3) {
+            if (t >= a.tile_hdr[3]) lds_tile_f8<2, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
+            else lds_tile_f8<1, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
+        } else if (t >= a.tile_hdr[3]) lds_tile<2, 4, KVD, AUX, 64, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
         else lds_tile<1, 4, KVD, AUX, 64, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
     } else if constexpr (S0 > 0) {
         if (t >= a.tile_hdr[1]) stream_tile<2, KVD, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)sm, tid);
