@@ -75,20 +75,27 @@ def read_traffic(name):
     return None
 
 
-def paper_sweep(steps, warmup):
+def paper_sweep(steps, warmup, full_scale=False):
     """Second workload: the paper's operating point (Sec. IV: fp8 store, 75 % routing sparsity,
-    batch growing to 256) at one-GPU scale -- shared and unique attention utilisation against batch
-    size, the measured counterpart of the paper's modelled Fig. 5.  One JSON line per batch."""
+    batch growing to 256) -- shared and unique attention utilisation against batch size, the measured
+    counterpart of the paper's modelled Fig. 5.  One JSON line per batch.
+    full_scale: the paper's own sizes as far as one GPU holds them: a 16M-token shared context (4096
+    chunks of 4096 tokens, top-k = 1024) and 64K unique tokens per request; otherwise a 256K-token
+    context (64 chunks, top-k = 16) and 8K unique tokens.  The store is generated once, for the
+    largest batch; smaller batches use its first requests."""
     import torch
     import paper_2511_06010_amd as moska
-    from moska_inputs import Problem, generate
-    for B in (1, 4, 16, 64, 256):
-        p = Problem(B=B, Hq=32, Hkv=8, D=128, C=64, L=4096, k=16, U=8192, kv_dtype="fp8",
-                    name=f"paper-point-b{B}")
-        inp = generate(p, seed=20251106, device="cuda")
+    from moska_inputs import Inputs, Problem, generate
+    shape = dict(C=4096, L=4096, k=1024, U=65536) if full_scale else dict(C=64, L=4096, k=16, U=8192)
+    tag = "paper-point-16M" if full_scale else "paper-point"
+    batches = (1, 4, 16, 64, 256)
+    pmax = Problem(B=batches[-1], Hq=32, Hkv=8, D=128, kv_dtype="fp8", name=f"{tag}-b{batches[-1]}", **shape)
+    full = generate(pmax, seed=20251106, device="cuda")
+    for B in batches:
+        p = pmax.with_(B=B, name=f"{tag}-b{B}")
+        inp = Inputs(p, full.Q[:B], full.E, full.Ks, full.Vs, full.scale_k, full.scale_v, full.Ku[:B], full.Vu[:B],
+                     full.unique_len[:B], full.cstar[:B])
         buf = moska.Buffers(p)
-        moska.route(p, inp.Q, inp.E, buf.ids, None, buf.ws)
-        moska.bucket(p, buf.ids, buf.bucket_off, buf.bucket_items, buf.ws)
 
         def timed(fn):
             for _ in range(warmup):
@@ -100,21 +107,27 @@ def paper_sweep(steps, warmup):
             e1.record()
             torch.cuda.synchronize()
             return e0.elapsed_time(e1) / steps
+        ms_r = timed(lambda: moska.route(p, inp.Q, inp.E, buf.ids, None, buf.ws))
+        ms_b = timed(lambda: moska.bucket(p, buf.ids, buf.bucket_off, buf.bucket_items, buf.ws))
         ms_s = timed(lambda: moska.shared_attn(p, inp.Q, inp.Ks, inp.Vs, inp.scale_k, inp.scale_v, buf.ids,
                                                buf.bucket_off, buf.bucket_items, buf.part_O, buf.part_LSE, buf.ws))
         ms_u = timed(lambda: moska.unique_attn(p, inp.Q, inp.Ku, inp.Vu, inp.unique_len, buf.part_O, buf.part_LSE,
                                                buf.ws))
+        ms_m = timed(lambda: moska.merge(p, buf.part_O, buf.part_LSE, buf.O, buf.LSE))
         w = algorithmic_work(p, buf.bucket_off.cpu())
         rows = (buf.bucket_off[1:] - buf.bucket_off[:-1]).float() * p.G
         print(json.dumps({
             "workload": p.name, "B": B, "rows_per_bucket_mean": round(float(rows.mean()), 1),
+            "route_ms": round(ms_r, 4), "bucket_ms": round(ms_b, 4), "merge_ms": round(ms_m, 4),
+            "merge_GBs": round(w["merge"]["bytes"] / ms_m / 1e6, 1),
             "shared_ms": round(ms_s, 4), "shared_TFLOPs": round(w["shared_attn"]["flops"] / ms_s / 1e9, 1),
             "shared_mfma_frac": round(w["shared_attn"]["flops"] / ms_s / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
             "shared_GBs": round(w["shared_attn"]["bytes"] / ms_s / 1e6, 1),
             "shared_hbm_frac": round(w["shared_attn"]["bytes"] / ms_s / 1e6 / HBM_PEAK_GBS, 4),
             "unique_ms": round(ms_u, 4), "unique_GBs": round(w["unique_attn"]["bytes"] / ms_u / 1e6, 1),
             "unique_hbm_frac": round(w["unique_attn"]["bytes"] / ms_u / 1e6 / HBM_PEAK_GBS, 4),
-            "unique_mfma_frac": round(w["unique_attn"]["flops"] / ms_u / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)}), flush=True)
+            "unique_mfma_frac": round(w["unique_attn"]["flops"] / ms_u / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "step_ms": round(ms_r + ms_b + ms_s + ms_u + ms_m, 4)}), flush=True)
         del inp, buf
         torch.cuda.empty_cache()
 
@@ -265,6 +278,9 @@ def main():
     ap.add_argument("--sweep-store", choices=["bf16", "fp8"], help="restrict --reuse-sweep to one store dtype")
     ap.add_argument("--paper-sweep", action="store_true",
                     help="instead of the benchmark line: utilisation against batch size at the paper's operating point")
+    ap.add_argument("--paper-scale", choices=["256K", "16M"], default="256K",
+                    help="--paper-sweep: shared context of 64 chunks (top-16, 8K unique tokens) or of 4096 chunks "
+                         "(top-1024, 64K unique tokens)")
     ap.add_argument("--calibrate", action="store_true", help="run the 1 GiB calibration copy and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -286,7 +302,7 @@ def main():
         reuse_sweep(args.steps, args.warmup, (args.sweep_store,) if args.sweep_store else ("bf16", "fp8"))
         return
     if args.paper_sweep:
-        paper_sweep(args.steps, args.warmup)
+        paper_sweep(args.steps, args.warmup, args.paper_scale == "16M")
         return
     p = config(args.config)
     if args.q_len > 1:

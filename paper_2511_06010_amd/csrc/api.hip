@@ -81,6 +81,8 @@ Workspace carve_workspace(const moska_problem_t &p, void *ws) {
     w.tile_hdr = (int32_t *)(base + o); o += align_up(8 * sizeof(int32_t));
     w.tiles = (int32_t *)(base + o);    o += align_up(2 * tmax * sizeof(int32_t));
     w.rank = (int32_t *)(base + o);     o += align_up(items * sizeof(int32_t));
+    const int nsl = bucket_slices(per_token(p));
+    w.slice_hist = (int32_t *)(base + o); o += align_up(nsl > 1 ? nb * nsl * sizeof(int32_t) : 0);
     w.off = (int32_t *)(base + o);      o += align_up((nb + 1) * sizeof(int32_t));
     w.items = (int32_t *)(base + o);    o += align_up(items * sizeof(int32_t));
     const int ns = unique_splits(p);
@@ -179,7 +181,7 @@ int moska_bucket(const moska_problem_t *p, const int32_t *ids, int32_t *bucket_o
     if (!ids || !bucket_off || !bucket_items || !ws) return MOSKA_ERR_INVALID_ARG;
     const Workspace w = carve_workspace(*p, ws);
     if (ws_bytes < w.bytes) return MOSKA_ERR_WORKSPACE_TOO_SMALL;
-    return launch_bucket(per_token(*p), ids, bucket_off, bucket_items, w.rank, (hipStream_t)stream);
+    return launch_bucket(per_token(*p), ids, bucket_off, bucket_items, w.rank, w.slice_hist, (hipStream_t)stream);
 }
 
 int moska_shared_attn(const moska_problem_t *p, const void *Q, const void *Ks, const void *Vs, const float *scale_k,
@@ -196,7 +198,7 @@ int moska_shared_attn(const moska_problem_t *p, const void *Q, const void *Ks, c
     if (ws_bytes < w.bytes) return MOSKA_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t s = (hipStream_t)stream;
     if (!bucket_off) {
-        if (int rc = launch_bucket(per_token(*p), ids, w.off, w.items, w.rank, s)) return rc;
+        if (int rc = launch_bucket(per_token(*p), ids, w.off, w.items, w.rank, w.slice_hist, s)) return rc;
         bucket_off = w.off;
         bucket_items = w.items;
     }

@@ -59,6 +59,7 @@ struct Workspace {
     int32_t *tile_hdr;
     int32_t *tiles;         // (bucket, first row) pairs, grouped by class
     int32_t *rank;          // moska_bucket scratch
+    int32_t *slice_hist;    // moska_bucket scratch of the multi-workgroup form: [Hkv][slices][C]
     int32_t *off;           // bucket_off when the caller passes none
     int32_t *items;
     float *split_O;         // [B,Hq,splits,D] partial outputs of a split unique attention
@@ -72,8 +73,11 @@ Workspace carve_workspace(const moska_problem_t &p, void *ws);
 
 int launch_route(const moska_problem_t &p, const void *Q, const void *E, int32_t *ids, float *scores, uint64_t *keys,
                  hipStream_t s);
+// Heads with very many items are bucketed by this many workgroups each (1: one workgroup per head);
+// p with one query token per request.
+int bucket_slices(const moska_problem_t &p);
 int launch_bucket(const moska_problem_t &p, const int32_t *ids, int32_t *off, int32_t *items,
-                  int32_t *rank_scratch, hipStream_t s);
+                  int32_t *rank_scratch, int32_t *slice_hist, hipStream_t s);
 int launch_tile_list(const moska_problem_t &p, const int32_t *off, const SharedPlan &pl, int32_t *hdr,
                      int32_t *tiles, hipStream_t s);
 

@@ -12,7 +12,8 @@
 // wave, lowest chunk id among its holders".  Up to 1024 chunks the keys stay in registers (lane l holds
 // chunks l, l+64, ...) and the wave-wide maximum / minimum run on the vector ALU (DPP permutes, then
 // v_permlane16_swap / v_permlane32_swap); above that the keys sit in LDS and only a round's winner
-// rescans its chunks.
+// rescans its chunks -- unless k is large too (the paper's 75 % sparsity keeps a quarter of thousands
+// of chunks): then a workgroup sorts the row's keys with a bitonic network and writes the first k.
 //
 // Head sizes other than 64/128/256 take a vector-ALU scoring kernel (one chunk row per lane).
 #include "moska_internal.h"
@@ -233,6 +234,79 @@ __global__ __launch_bounds__(256) void route_select_reg_kernel(const uint64_t *_
     }
 }
 
+// Selection by sorting, for many chunks AND a large k (the k-round selections above cost k wave-wide
+// reductions per row): one workgroup of 256 threads sorts the row's N = 256*EPT (key, chunk) pairs,
+// C padded with keys below every real one, into the order (key descending, chunk ascending) with a
+// bitonic network and writes the first k.  Thread t owns elements t*EPT .. t*EPT+EPT-1 in
+// registers: compare-exchange steps with a stride below EPT stay inside the thread; for the
+// others the threads swap elements through LDS (element e of thread t at [e][t]: conflict free).
+template <int EPT>
+__global__ __launch_bounds__(256) void route_sort_kernel(const uint64_t *__restrict__ gkeys, int32_t *__restrict__ ids,
+                                                          float *__restrict__ scores, int C, int k) {
+    constexpr int N = 256 * EPT;
+    __shared__ uint64_t xkey[EPT][256];
+    __shared__ int32_t xid[EPT][256];
+    const int t = threadIdx.x;
+    const int64_t r = blockIdx.x;                           // r = b*Hkv + h
+    uint64_t key[EPT];
+    int32_t id[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+        const int c = t * EPT + e;
+        key[e] = c < C ? gkeys[r * C + c] : 0;              // 0 is below every real key
+        id[e] = c < C ? c : 0x7FFFFFFF;
+    }
+    // a goes before b
+    auto before = [](uint64_t ka, int32_t ia, uint64_t kb, int32_t ib) { return ka > kb || (ka == kb && ia < ib); };
+#pragma unroll
+    for (int size = 2; size <= N; size <<= 1) {
+#pragma unroll
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            if (stride < EPT) {
+#pragma unroll
+                for (int e = 0; e < EPT; ++e) {
+                    if (e & stride) continue;               // the lower element of each pair does the exchange
+                    const int f = e | stride;
+                    const bool up = ((t * EPT + e) & size) == 0;          // this block is sorted best first
+                    const bool swap = before(key[f], id[f], key[e], id[e]) == up;
+                    const uint64_t ke = key[e], kf = key[f];
+                    const int32_t ie = id[e], jf = id[f];
+                    key[e] = swap ? kf : ke; key[f] = swap ? ke : kf;
+                    id[e] = swap ? jf : ie;  id[f] = swap ? ie : jf;
+                }
+            } else {
+                __syncthreads();                            // the previous exchange has been read
+#pragma unroll
+                for (int e = 0; e < EPT; ++e) {
+                    xkey[e][t] = key[e];
+                    xid[e][t] = id[e];
+                }
+                __syncthreads();
+                const int pt = t ^ (stride / EPT);          // the thread that owns the partners
+                const bool lower = (t & (stride / EPT)) == 0;
+#pragma unroll
+                for (int e = 0; e < EPT; ++e) {
+                    const bool up = ((t * EPT + e) & size) == 0;
+                    const uint64_t kp = xkey[e][pt];
+                    const int32_t ip = xid[e][pt];
+                    // keep the better of the two in the lower position of a best-first block, the worse otherwise
+                    const bool take = before(kp, ip, key[e], id[e]) == (up == lower);
+                    key[e] = take ? kp : key[e];
+                    id[e] = take ? ip : id[e];
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+        const int g = t * EPT + e;
+        if (g < k) {
+            ids[r * k + g] = id[e];
+            if (scores) scores[r * k + g] = (float)key_to_score(key[e]);
+        }
+    }
+}
+
 // Vector-ALU scoring for the other head sizes: one wave per (request, KV head), lane l scores
 // chunks l, l+64, ... with fp64 FMAs, then the same selection.
 template <int QD>
@@ -311,6 +385,13 @@ int launch_route(const moska_problem_t &p, const void *Q, const void *E, int32_t
             void *sargs[] = {&ck, &ids, &scores, &nrows, &C, &k};
             if (hipLaunchKernel(sel, dim3((unsigned)((rows + 3) / 4)), dim3(4 * kWave), sargs, 0, s) != hipSuccess)
                 return MOSKA_ERR_HIP;
+            return hip_status(hipGetLastError());
+        }
+        if (p.k > 32 && p.C <= 4096) {                      // many chunks and a large k: sort the row
+            const void *sel = p.C <= 2048 ? (const void *)route_sort_kernel<8> : (const void *)route_sort_kernel<16>;
+            const uint64_t *ck = keys;
+            void *sargs[] = {&ck, &ids, &scores, &C, &k};
+            if (hipLaunchKernel(sel, dim3((unsigned)rows), dim3(256), sargs, 0, s) != hipSuccess) return MOSKA_ERR_HIP;
             return hip_status(hipGetLastError());
         }
         const size_t per_wave = (size_t)p.C * sizeof(uint64_t);

@@ -63,6 +63,9 @@ SMALL = {
     "bf16-d48": P(D=48, B=7, Hq=4, Hkv=2, C=10, L=50, k=2, U=12),
     # bf16 with a head size the MFMA kernels do not cover (vector-ALU path)
     "bf16-d64": P(D=64, B=10, L=150, U=90),
+    # thousands of chunks and a large k (the paper's 75 % sparsity): routing by sorting, hundreds of partial slots
+    "bf16-route-sort-1500": P(B=6, Hq=8, Hkv=2, C=1500, L=6, k=300, U=10),
+    "fp8-route-sort-4096": P(kv_dtype="fp8", B=3, Hq=8, Hkv=2, C=4096, L=3, k=1024, U=5),
     # fp8 shared store
     "fp8-base": P(kv_dtype="fp8", B=24, Hq=16, Hkv=2, C=6, L=300, k=2, U=100),
     "fp8-hot": P(kv_dtype="fp8", B=80, Hq=16, Hkv=2, C=2, L=128, k=1, U=16),
@@ -194,6 +197,20 @@ def test_bucket_handles_many_items_per_wave_slice():
     assert torch.equal(buf.bucket_off.cpu(), off) and torch.equal(buf.bucket_items.cpu(), items)
 
 
+def test_bucket_over_several_workgroups_per_head():
+    # 42 000 items per KV head: the head is bucketed by several workgroups (count, scan, scatter)
+    p = P(B=700, Hq=6, Hkv=3, C=300, k=60, L=16, U=0, D=64)
+    g = torch.Generator().manual_seed(4)
+    ids = torch.stack([torch.stack([torch.randperm(p.C, generator=g)[:p.k] for _ in range(p.Hkv)])
+                       for _ in range(p.B)]).to(torch.int32)
+    ids[:, 1, :] = ids[:, 1, :] % 7                  # a head whose items crowd into seven buckets (repeated ids)
+    off, items = oracle.bucket(p, ids)
+    buf = moska.Buffers(p)
+    moska.bucket(p, ids.cuda(), buf.bucket_off, buf.bucket_items, buf.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(buf.bucket_off.cpu(), off) and torch.equal(buf.bucket_items.cpu(), items)
+
+
 def test_repeated_chunk_ids_fill_every_slot():
     # ids chosen by the caller may name a chunk twice for one (request, KV head): both slots are work
     # items of the same bucket (a bucket then holds more rows than there are requests x group heads)
@@ -214,6 +231,26 @@ def test_repeated_chunk_ids_fill_every_slot():
     assert torch.equal(buf.bucket_off.cpu(), off) and torch.equal(buf.bucket_items.cpu(), items)
     assert_vectors_close(buf.part_O[:, :, :p.k], want_O[:, :, :p.k], "bf16", "repeated ids part_O")
     assert_lse_close(buf.part_LSE[:, :, :p.k], want_L[:, :, :p.k], "bf16", "repeated ids part_LSE")
+
+
+def test_merge_many_slots():
+    # hundreds of partial slots: the workgroup-per-row merge, with empty slots and an all-empty row
+    p = P(B=3, Hq=4, Hkv=2, C=400, k=300, D=128)
+    g = torch.Generator().manual_seed(6)
+    pO = torch.randn(p.B, p.Hq, p.k + 1, p.D, generator=g)
+    pL = torch.randn(p.B, p.Hq, p.k + 1, generator=g) * 3
+    pL[0, :, 5::7] = -math.inf
+    pL[1, 2] = -math.inf
+    pO[1, 2] = float("nan")
+    want_O, want_L = oracle.merge(torch.nan_to_num(pO), pL)
+    O = torch.empty(p.B, p.Hq, p.D, dtype=torch.bfloat16, device="cuda")
+    LSE = torch.empty(p.B, p.Hq, device="cuda")
+    moska.merge(p, pO.cuda(), pL.cuda(), O, LSE)
+    torch.cuda.synchronize()
+    assert (O[1, 2] == 0).all() and torch.isinf(LSE[1, 2])
+    torch.testing.assert_close(O.cpu().double(), want_O, rtol=0, atol=2e-2)
+    assert ((O.cpu().double() - want_O).norm() / want_O.norm()) < 5e-3
+    torch.testing.assert_close(LSE.cpu().double(), want_L, rtol=0, atol=1e-5)
 
 
 def test_merge_empty_slots():
@@ -399,7 +436,29 @@ def test_paper_operating_point_small():
     check_against_oracle(generate(p, seed=41, unique_len="ragged"), p.name)
 
 
+def test_route_by_sorting_ties_and_padding():
+    # C between two powers of two (the sort pads), exact ties across the k-th place, an all-zero query
+    p = P(B=5, Hq=8, Hkv=2, C=1100, L=2, k=400, U=1)
+    inp = generate(p, seed=17)
+    inp.E[:, 700:1100] = inp.E[:, 300:700]          # every score of chunks 300..699 appears twice
+    inp.Q[0] = 0
+    o_ids, _ = oracle.route(p, inp.Q, inp.E)
+    d = inp.to("cuda")
+    ids = torch.empty_like(o_ids, device="cuda")
+    moska.route(p, d.Q, d.E, ids, None, moska.Buffers(p).ws)
+    torch.cuda.synchronize()
+    assert torch.equal(ids.cpu(), o_ids)
+    assert ids[0, 0].cpu().tolist() == list(range(p.k))
+
+
 @pytest.mark.parametrize("B", [16, 256])
 def test_paper_operating_point_full_chunk_length(B):
     p = P(kv_dtype="fp8", B=B, Hq=32, Hkv=8, C=64, L=4096, k=16, U=8192, name=f"paper-point-b{B}")
     _full_size_check(p, 20251106, n_tokens=min(B, 64))
+
+
+def test_paper_operating_point_16M_shared_tokens():
+    # the paper's own shared context: 4096 chunks x 4096 tokens (16M tokens, 34 GB in fp8), top-k = 1024,
+    # 64K unique tokens per request; one KV head of each sampled token (its 1024 chunks are 1 GB)
+    p = P(kv_dtype="fp8", B=32, Hq=32, Hkv=8, C=4096, L=4096, k=1024, U=65536, name="paper-point-16M-b32")
+    _full_size_check(p, 20251106, n_tokens=6, heads_per_token=1)
