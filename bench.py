@@ -241,6 +241,44 @@ def extra_config(moska, torch, idx, steps, warmup):
     return out
 
 
+def offline(steps, warmup):
+    """The two cache-construction kernels (Sec. III-A/B: pre-computed shared store and chunk
+    embeddings) at the store of configuration 4 (512 chunks x 8 KV heads x 4096 tokens x 128):
+    quantisation of a bf16 store to fp8 and the chunk embeddings of the bf16 and of the fp8 store.
+    One JSON line per kernel; bytes are the algorithmic ones (every input element read once, every
+    output element written once)."""
+    import torch
+    import paper_2511_06010_amd as moska
+    from moska_inputs import config
+    p = config(4)
+    n = p.C * p.Hkv * p.L * p.D
+    g = torch.Generator(device="cuda").manual_seed(20251110)
+    X = torch.randn((p.C, p.Hkv, p.L, p.D), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    X8 = torch.empty(X.shape, dtype=torch.float8_e4m3fn, device="cuda")
+    sc = torch.empty((p.C, p.Hkv), dtype=torch.float32, device="cuda")
+    E = torch.empty((p.Hkv, p.C, p.D), dtype=torch.bfloat16, device="cuda")
+    pb = p.with_(kv_dtype="bf16")
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+    for name, fn, nbytes in (
+            ("moska_quantize_shared bf16->fp8", lambda: moska.quantize_shared(p, X, X8, sc), 3 * n),
+            ("moska_chunk_embeddings bf16 store", lambda: moska.chunk_embeddings(pb, X, None, E), 2 * n),
+            ("moska_chunk_embeddings fp8 store", lambda: moska.chunk_embeddings(p, X8, sc, E), n)):
+        ms = timed(fn)
+        print(json.dumps({"kernel": name, "store": f"{p.C}x{p.Hkv}x{p.L}x{p.D}", "ms": round(ms, 4),
+                          "algorithmic_GB": round(nbytes / 1e9, 3), "GB/s": round(nbytes / ms / 1e6, 1),
+                          "hbm_frac": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}), flush=True)
+
+
 def calibrate():
     """A plain device-to-device copy of 1 GiB (torch's copy kernel), 10 times: its FETCH_SIZE and
     WRITE_SIZE under `rocprofv3 --pmc` against the known 1 GiB each way give the factors by which the
@@ -281,6 +319,8 @@ def main():
     ap.add_argument("--paper-scale", choices=["256K", "16M"], default="256K",
                     help="--paper-sweep: shared context of 64 chunks (top-16, 8K unique tokens) or of 4096 chunks "
                          "(top-1024, 64K unique tokens)")
+    ap.add_argument("--offline", action="store_true",
+                    help="time the cache-construction kernels (quantisation, chunk embeddings) at config 4's store")
     ap.add_argument("--calibrate", action="store_true", help="run the 1 GiB calibration copy and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -297,6 +337,9 @@ def main():
     torch.cuda.set_device(0)
     if args.calibrate:
         calibrate()
+        return
+    if args.offline:
+        offline(args.steps, args.warmup)
         return
     if args.reuse_sweep:
         reuse_sweep(args.steps, args.warmup, (args.sweep_store,) if args.sweep_store else ("bf16", "fp8"))

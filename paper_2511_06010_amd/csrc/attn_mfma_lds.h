@@ -496,9 +496,10 @@ __device__ __forceinline__ void lds_tile_f8(const SharedArgs &a, int bkt, int ro
     store_rows<NR, !SPLIT>(st, q, orow, vmul, SPLIT ? a.split_O : a.part_O, SPLIT ? a.split_LSE : a.part_LSE);
 }
 
-// The whole tile list in ONE launch of 512-thread workgroups, so that no size class pays a kernel's
-// fill and drain of its own and the long 256-row tiles run beside the streaming ones.  Three kinds
-// of work item:
+// The tile list in ONE launch of 512-thread workgroups (pairs != 0), so that no size class pays a
+// kernel's fill and drain of its own and the long 256-row tiles run beside the streaming ones; or
+// only its 256-row tiles (pairs == 0), the others going to shared_small_kernel.  Three kinds of
+// work item:
 //   256-row tile        one per workgroup (8 waves x 32 rows)
 //   staged pair         two LDS-staged tiles of up to 128 rows per workgroup, one per half (4 waves
 //                       each, with its own half of the LDS); both halves stream chunks of the same
@@ -509,7 +510,7 @@ __device__ __forceinline__ void lds_tile_f8(const SharedArgs &a, int bkt, int ro
 // The grid is sized on the host from upper bounds; workgroups beyond the items that exist return.
 // A half without a tile of its own repeats its sibling's (same values to the same slots).
 template <int KVD, int AUX, bool SPLIT>
-__global__ __launch_bounds__(512, 2) void shared_all_kernel(SharedArgs a, int Hq, int Hkv, int C,
+__global__ __launch_bounds__(512, 2) void shared_all_kernel(SharedArgs a, int pairs, int Hq, int Hkv, int C,
                                                              int L, int k, float scale) {
     constexpr int HALF = lds_units<64>();                   // 64 KiB of K/V stages, or a 33 KiB merge buffer
     __shared__ uint4 smem[2 * HALF];
@@ -519,7 +520,7 @@ __global__ __launch_bounds__(512, 2) void shared_all_kernel(SharedArgs a, int Hq
     // (workgroups are dealt to the 8 XCDs round-robin) takes a contiguous share of each list, so that
     // the tiles of one bucket, which re-read the same chunk, share an L2
     const int n4 = a.tile_hdr[5] - a.tile_hdr[4], nL = a.tile_hdr[4] - a.tile_hdr[S0], nS = a.tile_hdr[S0] - a.tile_hdr[0];
-    const int p4 = (n4 + 7) >> 3, pL = (((nL + 1) >> 1) + 7) >> 3, pS = (((nS + 1) >> 1) + 7) >> 3;
+    const int p4 = (n4 + 7) >> 3, pL = pairs ? (((nL + 1) >> 1) + 7) >> 3 : 0, pS = pairs ? (((nS + 1) >> 1) + 7) >> 3 : 0;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, per = p4 + pL + pS;
     if (slot >= per) return;
     // slot -> (kind, index inside the XCD's share): the long 256-row tiles first.  (Spreading them
@@ -546,6 +547,30 @@ __global__ __launch_bounds__(512, 2) void shared_all_kernel(SharedArgs a, int Hq
     const int t = a.tile_hdr[staged ? 4 : S0] - 1 - i;      // each list is walked from its end: largest tiles first
     const int bkt = a.tiles[2 * t], row0 = a.tiles[2 * t + 1];
     if (staged) {
+        if constexpr (KVD == MOSKA_FP8_E4M3) {
+            if (t >= a.tile_hdr[3]) lds_tile_f8<2, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
+            else lds_tile_f8<1, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
+        } else if (t >= a.tile_hdr[3]) lds_tile<2, 4, KVD, AUX, 64, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
+        else lds_tile<1, 4, KVD, AUX, 64, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
+    } else if constexpr (S0 > 0) {
+        if (t >= a.tile_hdr[1]) stream_tile<2, KVD, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)sm, tid);
+        else stream_tile<1, KVD, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)sm, tid);
+    }
+}
+
+// The tiles of up to 128 rows, one per 256-thread workgroup (two workgroups share a compute unit and
+// run independently of each other).
+template <int KVD, int AUX, bool SPLIT>
+__global__ __launch_bounds__(256, 2) void shared_small_kernel(SharedArgs a, int Hq, int Hkv, int C, int L, int k,
+                                                               float scale) {
+    __shared__ uint4 sm[lds_units<64>()];
+    constexpr int S0 = KVD == MOSKA_FP8_E4M3 ? 2 : 0;
+    const int n = a.tile_hdr[4] - a.tile_hdr[0];
+    const int w = xcd_tile_index(blockIdx.x, n);
+    if (w < 0) return;
+    const int t = a.tile_hdr[4] - 1 - w;                    // walked from the end: largest tiles first
+    const int bkt = a.tiles[2 * t], row0 = a.tiles[2 * t + 1], tid = threadIdx.x;
+    if (t >= a.tile_hdr[S0]) {
         if constexpr (KVD == MOSKA_FP8_E4M3) {
             if (t >= a.tile_hdr[3]) lds_tile_f8<2, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
             else lds_tile_f8<1, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);

@@ -7,23 +7,40 @@
 namespace moska {
 namespace mfma {
 
-// One launch serves every tile (shared_all_kernel): workgroups for the 256-row tiles, for pairs of
-// LDS-staged small tiles and, for an fp8 store, for pairs of streaming tiles, each count taken from
-// the host-side bound on the tiles of that kind and rounded up to a multiple of 8.
+// shared_all_kernel serves the 256-row tiles and, when the small tiles go in pairs, those too:
+// workgroups for the 256-row tiles, for pairs of LDS-staged small tiles and, for an fp8 store, for
+// pairs of streaming tiles, each count taken from the host-side bound on the tiles of that kind and
+// rounded up to a multiple of 8.
 template <int KVD>
 int launch_shared_classes(const moska_problem_t &p, const SharedArgs &a, const SharedPlan &pl, hipStream_t s) {
     constexpr int S0 = KVD == MOSKA_FP8_E4M3 ? 2 : 0;       // first class of the LDS-staged small tiles
     const int64_t b4 = tiles_bound(p, pl, 4, 4), bL = tiles_bound(p, pl, S0, 3), bS = S0 > 0 ? tiles_bound(p, pl, 0, S0 - 1) : 0;
     auto blocks = [](int64_t work) { return (work + 7) / 8 * 8; };
-    const int64_t grid = blocks(b4) + blocks((bL + 1) / 2) + blocks((bS + 1) / 2);
-    if (grid == 0) return MOSKA_OK;
+    // Small tiles two to a 512-thread workgroup in the same launch as the 256-row tiles, or one to a
+    // 256-thread workgroup in a launch of their own.  The two halves of a pair run in lock step (one
+    // barrier), so their MFMA phases coincide: measured 3-4 % faster where the small tiles are light
+    // (about 32 rows per bucket: 256 requests x top-8 of 256 chunks) or the remainders of an fp8 store's
+    // large buckets, 4-8 % slower where they carry 64-128 rows each (1024 requests x top-16 of 1024
+    // chunks) and when chunks are split over workgroups (small batches).
+    static const int forced = tuning_env("MOSKA_SHARED_PAIRED", -1);
+    const double mean_rows = (double)p.B * p.k * (p.Hq / p.Hkv) / p.C;
+    int paired = forced >= 0 ? forced : (a.nsplit == 1 && (KVD == MOSKA_FP8_E4M3 || mean_rows <= 48.0));
+    const int64_t grid = blocks(b4) + (paired ? blocks((bL + 1) / 2) + blocks((bS + 1) / 2) : 0);
     int Hq = p.Hq, Hkv = p.Hkv, C = p.C, L = p.L, k = p.k;
     float scale = p.scale;
     SharedArgs args = a;
-    void *kargs[] = {&args, &Hq, &Hkv, &C, &L, &k, &scale};
+    void *kargs[] = {&args, &paired, &Hq, &Hkv, &C, &L, &k, &scale};
     const void *kern = a.nsplit > 1 ? (const void *)shared_all_kernel<KVD, 2, true>
                                     : (const void *)shared_all_kernel<KVD, 2, false>;
-    if (hipLaunchKernel(kern, dim3((unsigned)grid, a.nsplit), dim3(512), kargs, 0, s) != hipSuccess) return MOSKA_ERR_HIP;
+    if (grid > 0 && hipLaunchKernel(kern, dim3((unsigned)grid, a.nsplit), dim3(512), kargs, 0, s) != hipSuccess)
+        return MOSKA_ERR_HIP;
+    if (!paired && bL + bS > 0) {
+        void *sargs[] = {&args, &Hq, &Hkv, &C, &L, &k, &scale};
+        const void *sk = a.nsplit > 1 ? (const void *)shared_small_kernel<KVD, 2, true>
+                                      : (const void *)shared_small_kernel<KVD, 2, false>;
+        if (hipLaunchKernel(sk, dim3((unsigned)blocks(bL + bS), a.nsplit), dim3(256), sargs, 0, s) != hipSuccess)
+            return MOSKA_ERR_HIP;
+    }
     return MOSKA_OK;
 }
 

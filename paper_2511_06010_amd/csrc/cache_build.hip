@@ -24,10 +24,12 @@ __device__ __forceinline__ void unpack16(const uint4 &u, float *v) {
             v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
         }
     } else {
+        typedef __attribute__((ext_vector_type(2))) float f32x2;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[4 * i + j] = fp8_e4m3fn_to_f32((w[i] >> (8 * j)) & 0xFFu);
+        for (int i = 0; i < 4; ++i) {                       // v_cvt_pk_f32_fp8: two bytes per instruction, exact
+            const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);
+            v[4 * i] = lo[0]; v[4 * i + 1] = lo[1]; v[4 * i + 2] = hi[0]; v[4 * i + 3] = hi[1];
+        }
     }
 }
 
@@ -47,11 +49,30 @@ __global__ __launch_bounds__(256) void chunk_embeddings_kernel(const void *__res
 #pragma unroll
     for (int i = 0; i < N; ++i) acc[i] = 0.0;
     if (r < R) {
-        for (int t = r; t < L; t += R) {
-            float v[N];
-            unpack16<KVD>(base[(int64_t)t * upr + u], v);
+        if constexpr (KVD == MOSKA_FP8_E4M3) {
+            // e4m3 values are multiples of 2^-9 of magnitude <= 448: 32 of them add up exactly in f32
+            // (23 bits), so the fp64 accumulator is touched once per 32 rows; every sum here is exact
+            // in any order, and so is the reference's.
+            for (int t0 = r; t0 < L; t0 += 32 * R) {
+                float part[N];
 #pragma unroll
-            for (int i = 0; i < N; ++i) acc[i] += (double)v[i];
+                for (int i = 0; i < N; ++i) part[i] = 0.f;
+                for (int t = t0; t < min(L, t0 + 32 * R); t += R) {
+                    float v[N];
+                    unpack16<KVD>(base[(int64_t)t * upr + u], v);
+#pragma unroll
+                    for (int i = 0; i < N; ++i) part[i] += v[i];
+                }
+#pragma unroll
+                for (int i = 0; i < N; ++i) acc[i] += (double)part[i];
+            }
+        } else {
+            for (int t = r; t < L; t += R) {
+                float v[N];
+                unpack16<KVD>(base[(int64_t)t * upr + u], v);
+#pragma unroll
+                for (int i = 0; i < N; ++i) acc[i] += (double)v[i];
+            }
         }
 #pragma unroll
         for (int i = 0; i < N; ++i) red[r * D + u * N + i] = acc[i];
