@@ -389,7 +389,7 @@ constexpr int lds_units_f8() { return 2 * 64 * 8 + 2 * 64 * 16; }
 template <int NR, int NWV, int AUX, int PD, bool SPLIT>
 __device__ __forceinline__ void lds_tile_f8(const SharedArgs &a, int bkt, int row0, int Hq, int Hkv, int C, int Lchunk,
                                             int k, float scale, uint4 *smem, int tid) {
-    static_assert(PD == 1 || PD == 2, "stages in flight");
+    static_assert(PD == 1 || PD == 2 || PD == 4, "stages in flight");
     constexpr int KVD = MOSKA_FP8_E4M3, KT = 64, T = NWV * 64;
     constexpr int KU = KT * 8, VU = KT * 16;                // uint4 units of a K stage and of a V stage
     uint4 *ldsK = smem, *ldsV = smem + 2 * KU;
@@ -496,6 +496,28 @@ __device__ __forceinline__ void lds_tile_f8(const SharedArgs &a, int bkt, int ro
     store_rows<NR, !SPLIT>(st, q, orow, vmul, SPLIT ? a.split_O : a.part_O, SPLIT ? a.split_LSE : a.part_LSE);
 }
 
+// A tile of up to 128 rows on the LDS-staged path, by the 256 threads tid = 0 .. 255 that share sm
+// (64 KiB): 4 waves x 16 rows (up to 64 rows) or 4 waves x 32 rows.  One stage of loads in flight:
+// two or four measured the same to within 2 % for either store (these tiles are bound by what a
+// compute unit gets done per stage, not by the latency of its loads).
+#ifndef MOSKA_PD_F8
+#define MOSKA_PD_F8 1
+#endif
+#ifndef MOSKA_PD_B16
+#define MOSKA_PD_B16 1
+#endif
+template <int KVD, int AUX, bool SPLIT>
+__device__ __forceinline__ void staged_small_tile(const SharedArgs &a, bool rows128, int bkt, int row0, int Hq, int Hkv,
+                                                  int C, int L, int k, float scale, uint4 *sm, int tid) {
+    if constexpr (KVD == MOSKA_FP8_E4M3) {
+        if (rows128) lds_tile_f8<2, 4, AUX, MOSKA_PD_F8, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
+        else lds_tile_f8<1, 4, AUX, MOSKA_PD_F8, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
+    } else {
+        if (rows128) lds_tile<2, 4, KVD, AUX, 64, MOSKA_PD_B16, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
+        else lds_tile<1, 4, KVD, AUX, 64, MOSKA_PD_B16, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
+    }
+}
+
 // The tile list in ONE launch of 512-thread workgroups (pairs != 0), so that no size class pays a
 // kernel's fill and drain of its own and the long 256-row tiles run beside the streaming ones; or
 // only its 256-row tiles (pairs == 0), the others going to shared_small_kernel.  Three kinds of
@@ -547,11 +569,7 @@ __global__ __launch_bounds__(512, 2) void shared_all_kernel(SharedArgs a, int pa
     const int t = a.tile_hdr[staged ? 4 : S0] - 1 - i;      // each list is walked from its end: largest tiles first
     const int bkt = a.tiles[2 * t], row0 = a.tiles[2 * t + 1];
     if (staged) {
-        if constexpr (KVD == MOSKA_FP8_E4M3) {
-            if (t >= a.tile_hdr[3]) lds_tile_f8<2, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
-            else lds_tile_f8<1, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
-        } else if (t >= a.tile_hdr[3]) lds_tile<2, 4, KVD, AUX, 64, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
-        else lds_tile<1, 4, KVD, AUX, 64, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
+        staged_small_tile<KVD, AUX, SPLIT>(a, t >= a.tile_hdr[3], bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
     } else if constexpr (S0 > 0) {
         if (t >= a.tile_hdr[1]) stream_tile<2, KVD, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)sm, tid);
         else stream_tile<1, KVD, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)sm, tid);
@@ -571,11 +589,7 @@ __global__ __launch_bounds__(256, 2) void shared_small_kernel(SharedArgs a, int 
     const int t = a.tile_hdr[4] - 1 - w;                    // walked from the end: largest tiles first
     const int bkt = a.tiles[2 * t], row0 = a.tiles[2 * t + 1], tid = threadIdx.x;
     if (t >= a.tile_hdr[S0]) {
-        if constexpr (KVD == MOSKA_FP8_E4M3) {
-            if (t >= a.tile_hdr[3]) lds_tile_f8<2, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
-            else lds_tile_f8<1, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
-        } else if (t >= a.tile_hdr[3]) lds_tile<2, 4, KVD, AUX, 64, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
-        else lds_tile<1, 4, KVD, AUX, 64, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
+        staged_small_tile<KVD, AUX, SPLIT>(a, t >= a.tile_hdr[3], bkt, row0, Hq, Hkv, C, L, k, scale, sm, tid);
     } else if constexpr (S0 > 0) {
         if (t >= a.tile_hdr[1]) stream_tile<2, KVD, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)sm, tid);
         else stream_tile<1, KVD, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)sm, tid);

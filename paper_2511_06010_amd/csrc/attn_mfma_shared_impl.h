@@ -17,14 +17,19 @@ int launch_shared_classes(const moska_problem_t &p, const SharedArgs &a, const S
     const int64_t b4 = tiles_bound(p, pl, 4, 4), bL = tiles_bound(p, pl, S0, 3), bS = S0 > 0 ? tiles_bound(p, pl, 0, S0 - 1) : 0;
     auto blocks = [](int64_t work) { return (work + 7) / 8 * 8; };
     // Small tiles two to a 512-thread workgroup in the same launch as the 256-row tiles, or one to a
-    // 256-thread workgroup in a launch of their own.  The two halves of a pair run in lock step (one
-    // barrier), so their MFMA phases coincide: measured 3-4 % faster where the small tiles are light
-    // (about 32 rows per bucket: 256 requests x top-8 of 256 chunks) or the remainders of an fp8 store's
-    // large buckets, 4-8 % slower where they carry 64-128 rows each (1024 requests x top-16 of 1024
-    // chunks) and when chunks are split over workgroups (small batches).
+    // 256-thread workgroup in a launch of their own (then up to three workgroups share a compute unit
+    // and run independently; the halves of a pair run in lock step behind one barrier).  Measured: pairs
+    // are 3-4 % faster where most rows sit in 256-row tiles and the small tiles are their remainders
+    // (fp8 store, 2048 requests x top-8 of 512 chunks) and for light bf16 tiles (about 32 rows per bucket:
+    // 256 requests x top-8 of 256 chunks); independent workgroups are 4-8 % faster for bf16 tiles of
+    // 64-128 rows (1024 requests x top-16 of 1024 chunks) and up to 35 % faster when the whole launch is
+    // only a few workgroups per compute unit or the tiles of an fp8 store carry few rows.
     static const int forced = tuning_env("MOSKA_SHARED_PAIRED", -1);
     const double mean_rows = (double)p.B * p.k * (p.Hq / p.Hkv) / p.C;
-    int paired = forced >= 0 ? forced : (a.nsplit == 1 && (KVD == MOSKA_FP8_E4M3 || mean_rows <= 48.0));
+    const int64_t items = (int64_t)p.B * p.Hkv * p.k, nb = (int64_t)p.Hkv * p.C;
+    const bool many = (items < nb ? items : nb) >= 1024;    // buckets that can be non-empty: >= 4 per compute unit
+    int paired = forced >= 0 ? forced
+                             : (many && a.nsplit == 1 && (KVD == MOSKA_FP8_E4M3 ? mean_rows >= 128.0 : mean_rows <= 48.0));
     const int64_t grid = blocks(b4) + (paired ? blocks((bL + 1) / 2) + blocks((bS + 1) / 2) : 0);
     int Hq = p.Hq, Hkv = p.Hkv, C = p.C, L = p.L, k = p.k;
     float scale = p.scale;
