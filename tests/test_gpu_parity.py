@@ -66,6 +66,10 @@ SMALL = {
     # thousands of chunks and a large k (the paper's 75 % sparsity): routing by sorting, hundreds of partial slots
     "bf16-route-sort-1500": P(B=6, Hq=8, Hkv=2, C=1500, L=6, k=300, U=10),
     "fp8-route-sort-4096": P(kv_dtype="fp8", B=3, Hq=8, Hkv=2, C=4096, L=3, k=1024, U=5),
+    # thousands of buckets: the small tiles go two to a workgroup, in one launch with the 256-row tiles
+    # (light bf16 tiles; an fp8 store whose rows sit mostly in large buckets, skewed popularity)
+    "bf16-paired-light": P(B=256, Hq=8, Hkv=2, C=1024, L=70, k=8, U=8, popularity="zipf", zipf_s=1.1),
+    "fp8-paired-remainders": P(kv_dtype="fp8", B=512, Hq=8, Hkv=2, C=512, L=40, k=32, U=4, popularity="zipf", zipf_s=1.1),
     # fp8 shared store
     "fp8-base": P(kv_dtype="fp8", B=24, Hq=16, Hkv=2, C=6, L=300, k=2, U=100),
     "fp8-hot": P(kv_dtype="fp8", B=80, Hq=16, Hkv=2, C=2, L=128, k=1, U=16),
