@@ -365,7 +365,7 @@ int launch_route(const moska_problem_t &p, const void *Q, const void *E, int32_t
     const void *score = p.q_dtype == MOSKA_BF16 ? score_kernel_for<MOSKA_BF16>(p.D) : score_kernel_for<MOSKA_F32>(p.D);
     // a small problem is bound by launch latency: scoring and selection in one kernel, on the vector ALU
     static const int64_t lane_limit = tuning_env("MOSKA_ROUTE_LANE_LIMIT", 4 << 20);
-    if (rows * p.C * p.D <= lane_limit) score = nullptr;
+    if (rows * p.C * p.D <= lane_limit && p.k <= 32 && p.C <= 1024) score = nullptr;
     if (score) {
         int B = p.B, Hq = p.Hq, Hkv = p.Hkv, C = p.C, k = p.k;
         int btiles = (p.B + 15) / 16, ctiles = (p.C + 15) / 16;
