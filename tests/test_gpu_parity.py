@@ -119,6 +119,32 @@ def test_random_small_problems():
         check_against_oracle(generate(p, seed=3000 + i, unique_len=ragged), f"random{i}")
 
 
+def test_random_problems_with_paired_small_tiles():
+    # seeded random shapes with thousands of buckets, where the small tiles of shared attention go two to a
+    # workgroup in the launch of the 256-row tiles: light bf16 tiles, and fp8 stores whose rows sit mostly in
+    # large buckets; short chunks keep the oracle fast
+    import random
+    rng = random.Random(77)
+    for i in range(8):
+        fp8 = i % 2 == 1
+        Hkv, G = rng.choice([(2, 4), (4, 2), (8, 1), (2, 8)])
+        C = rng.choice([512, 700, 1024]) if not fp8 else rng.choice([128, 256, 512])
+        while Hkv * C < 1024:
+            C *= 2
+        L = rng.choice([33, 64, 70, 130])
+        if fp8:                                   # expected rows per bucket B*k*G/C >= 128
+            k = rng.choice([8, 16, 32])
+            B = -(-128 * C // (k * G)) + rng.randint(0, 40)
+        else:                                     # <= 48
+            k = rng.choice([4, 8])
+            B = max(1024 // (Hkv * k) + 1, min(2000, rng.choice([12, 25, 40]) * C // (k * G)))
+        p = P(kv_dtype="fp8" if fp8 else "bf16", B=B, Hq=Hkv * G, Hkv=Hkv, C=C, L=L, k=k, U=rng.choice([0, 5, 40]),
+              popularity=rng.choice(["uniform", "zipf"]), zipf_s=1.2)
+        assert min(p.B * p.Hkv * p.k, p.Hkv * p.C) >= 1024
+        print(f"paired case {i}: {p}", flush=True)
+        check_against_oracle(generate(p, seed=4000 + i, unique_len="ragged"), f"paired{i}")
+
+
 def test_config0_matches_stored_oracle_values():
     # expected values stored by tests/golden/make_config0_golden.py (oracle only)
     from test_oracle_pins import read_config0_golden
@@ -318,6 +344,9 @@ def test_decode_step_replays_from_a_hip_graph():
         return buf.O.view(torch.uint8).clone(), buf.ids.clone()
 
     want = {0: eager_bits()}
+    # the eager result the replays are compared with is itself held against the oracle
+    st = oracle.decode_step(generate(p, seed=31), ids=want[0][1].cpu())
+    assert_vectors_close(buf.O, st.O_direct, "bf16", "eager decode_step O")
     saved_q = inp.Q.clone()
     inp.Q.copy_(other.Q)
     want[1] = eager_bits()
