@@ -39,7 +39,8 @@
  *     decode query sees every token of every selected chunk and of its unique context.
  *   - Accumulation is fp32 (fp64 for routing scores).  With q_dtype = MOSKA_F32 all
  *     arithmetic is fp32 on the vector ALUs; with MOSKA_BF16 and D = 128 the two
- *     attention calls run on bf16 MFMA with fp32 accumulation.
+ *     attention calls run on bf16 MFMA with fp32 accumulation (an FP8 store's scores on
+ *     the scaled fp8 MFMA, the query carried as a pair of e4m3 values: bf16 precision).
  */
 #ifndef MOSKA_H
 #define MOSKA_H

@@ -6,8 +6,9 @@
 // ALL keys of the chunk, so no cross-wave merge is needed.  The chunk's K and V are streamed
 // from HBM once per workgroup: every thread fetches a slice of the next KT-key stage into
 // registers while the current stage is consumed from LDS, then writes its slice to the other
-// LDS buffer (an fp8 store is widened to bf16 here, once per workgroup instead of once per
-// wave).  One barrier per stage.
+// LDS buffer.  One barrier per stage.  lds_tile serves a bf16 store; lds_tile_f8 an fp8 store, whose
+// keys stay fp8 in LDS for the scaled fp8 MFMA while its values are widened to bf16 on the way in
+// (once per workgroup, not once per wave); shared_all_kernel / shared_small_kernel are the launches.
 //
 // LDS stage layout (bf16): K[keys][256 B] with the 16-byte units of a row XOR-swizzled by
 // (key & 15), so the MFMA A-operand read (16 keys x one unit, 16 lanes per phase) is free of bank
@@ -56,21 +57,10 @@ __device__ __forceinline__ void stage_store(const StageRegs<KVD, T, KT> &r, uint
 #pragma unroll
     for (int i = 0; i < N; ++i) {
         const int g = tid + i * T;
-        if constexpr (KVD == MOSKA_BF16) {
-            const int row = g >> 4, u = g & 15;
-            lk[row * 16 + (u ^ (row & 15))] = r.k[i];
-            lv[row * 16 + ((((u >> 1) ^ (row & 7)) << 1) | (u & 1))] = r.v[i];
-        } else {
-            const int row = g >> 3, u = (g & 7) * 2;       // 8 fp8 units per key row -> bf16 units u, u+1
-            uint4 lo, hi;
-            fp8x16_to_bf16(r.k[i], lo, hi);
-            lk[row * 16 + (u ^ (row & 15))] = lo;
-            lk[row * 16 + ((u + 1) ^ (row & 15))] = hi;
-            fp8x16_to_bf16(r.v[i], lo, hi);
-            const int vb = ((g & 7) ^ (row & 7)) * 2;   // 32-byte block swizzle of the value rows
-            lv[row * 16 + vb] = lo;
-            lv[row * 16 + vb + 1] = hi;
-        }
+        static_assert(KVD == MOSKA_BF16, "an fp8 store is staged by lds_tile_f8");
+        const int row = g >> 4, u = g & 15;
+        lk[row * 16 + (u ^ (row & 15))] = r.k[i];
+        lv[row * 16 + ((((u >> 1) ^ (row & 7)) << 1) | (u & 1))] = r.v[i];
     }
 }
 

@@ -1,4 +1,5 @@
-// MFMA Shared KV Attention, fp8-e4m3 shared store (keys and values widened to bf16 in registers).
+// MFMA Shared KV Attention, fp8-e4m3 shared store (scores on the scaled fp8 MFMA from keys that stay fp8; values
+// widened to bf16 for the P V product).
 #include "attn_mfma_shared_impl.h"
 namespace moska {
 int launch_shared_mfma_fp8(const moska_problem_t &p, const SharedArgs &a, const SharedPlan &pl, hipStream_t s) {
