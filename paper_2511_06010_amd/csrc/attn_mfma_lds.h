@@ -123,7 +123,7 @@ template <int KT> constexpr int lds_units() { return 4 * KT * 16; }
 template <int NR, int NWV, int KVD, int AUX, int KT, int PD, bool SPLIT>
 __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0, int Hq, int Hkv, int C, int Lchunk,
                                          int k, float scale, uint4 *smem, int tid) {
-    static_assert(KT == 32 || KT == 64, "keys per stage");
+    static_assert(KT == 32 || KT == 64 || KT == 128, "keys per stage");
     static_assert(PD == 1 || PD == 2 || PD == 4, "stages in flight");
     constexpr int T = NWV * 64;
     constexpr int SU = KT * 16;                            // uint4 units of K (or V) per stage
@@ -244,6 +244,15 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
 // block scales of a row are taken from the scale registers of the row's four lanes, which hold
 // one common value here.
 typedef __attribute__((ext_vector_type(8))) int i32x8;
+// The 256-row tile of an fp8 store takes stages of 128 keys (96 KiB of LDS: half as many barriers; +4 % at 4096
+// rows per bucket) with one stage of loads in flight; for a bf16 store 128-key stages fill all 128 KiB and measured
+// 25 % slower, so it stays at 64 keys with two stages in flight.
+#ifndef MOSKA_BIG_KT
+#define MOSKA_BIG_KT 128
+#endif
+#ifndef MOSKA_BIG_PD
+#define MOSKA_BIG_PD 1
+#endif
 
 __device__ __forceinline__ f32x4 mfma_f8(const i32x8 &a, const i32x8 &b, f32x4 c, int scale_b) {
     return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0, 0, 0, 0x7F7F7F7F, 0, scale_b);
@@ -370,17 +379,19 @@ __device__ __forceinline__ void softmax_presub(WaveState<NR> &st, f32x4 (&negm)[
     }
 }
 
-// LDS of the fp8 tile, in uint4 units: two buffers of 64-key stages, keys as fp8 (8 units a key), values as bf16 (16)
-constexpr int lds_units_f8() { return 2 * 64 * 8 + 2 * 64 * 16; }
+// LDS of the fp8 tile, in uint4 units: two buffers of KT-key stages, keys as fp8 (8 units a key), values as bf16 (16)
+constexpr int lds_units_f8(int KT) { return 2 * KT * 8 + 2 * KT * 16; }
 
 // Tile (bkt, row0) of an fp8 store on the LDS-staged path with fp8 scores: 16*NR*NWV rows, by the
-// NWV*64 threads tid = 0 .. NWV*64-1 that share smem (lds_units_f8() uint4); stages of 64 keys, PD
-// (1 or 2) stages of global loads in flight.  One workgroup barrier per stage plus one, as lds_tile.
-template <int NR, int NWV, int AUX, int PD, bool SPLIT>
+// NWV*64 threads tid = 0 .. NWV*64-1 that share smem (two buffers of KT keys x 8 uint4 and of KT values x 16
+// uint4); stages of KT = 64 or 128 keys, PD (1, 2 or 4) stages of global loads in flight.  One workgroup barrier per stage plus one, as lds_tile.
+template <int NR, int NWV, int AUX, int PD, bool SPLIT, int KT = 64>
 __device__ __forceinline__ void lds_tile_f8(const SharedArgs &a, int bkt, int row0, int Hq, int Hkv, int C, int Lchunk,
                                             int k, float scale, uint4 *smem, int tid) {
     static_assert(PD == 1 || PD == 2 || PD == 4, "stages in flight");
-    constexpr int KVD = MOSKA_FP8_E4M3, KT = 64, T = NWV * 64;
+    static_assert(KT == 64 || KT == 128, "keys per stage");
+    static_assert(lds_units_f8(KT) <= (NWV == 8 ? 2 : 1) * lds_units<64>(), "a half workgroup has 64 KiB, a whole one 128");
+    constexpr int KVD = MOSKA_FP8_E4M3, T = NWV * 64;
     constexpr int KU = KT * 8, VU = KT * 16;                // uint4 units of a K stage and of a V stage
     uint4 *ldsK = smem, *ldsV = smem + 2 * KU;
     const int h = bkt / C, c = bkt - h * C, G = Hq / Hkv;
@@ -542,7 +553,7 @@ __global__ __launch_bounds__(512, 2) void shared_all_kernel(SharedArgs a, int pa
         if (w >= n4) return;
         const int t = a.tile_hdr[4] + w;
         if constexpr (KVD == MOSKA_FP8_E4M3)
-            lds_tile_f8<2, 8, AUX, 2, SPLIT>(a, a.tiles[2 * t], a.tiles[2 * t + 1], Hq, Hkv, C, L, k, scale, smem, threadIdx.x);
+            lds_tile_f8<2, 8, AUX, MOSKA_BIG_PD, SPLIT, MOSKA_BIG_KT>(a, a.tiles[2 * t], a.tiles[2 * t + 1], Hq, Hkv, C, L, k, scale, smem, threadIdx.x);
         else
             lds_tile<2, 8, KVD, AUX, 64, 2, SPLIT>(a, a.tiles[2 * t], a.tiles[2 * t + 1], Hq, Hkv, C, L, k, scale, smem,
                                                    threadIdx.x);
