@@ -118,7 +118,16 @@ def check_against_oracle(inp_cpu: Inputs, label: str = ""):
     if not excused:
         fb = gpu_pipeline(inp, fused=True)
         assert torch.equal(fb.ids, buf.ids) and torch.equal(fb.bucket_items, buf.bucket_items)
+        assert torch.equal(fb.bucket_off, buf.bucket_off), f"{label} decode_step bucket_off"
         assert torch.equal(fb.O.view(torch.uint8), buf.O.view(torch.uint8)), f"{label} decode_step != five calls"
+        # shared attention that makes its own bucket lists from ids
+        own = moska.Buffers(p)
+        moska.shared_attn(p, inp.Q, inp.Ks, inp.Vs, inp.scale_k, inp.scale_v, buf.ids, None, None, own.part_O,
+                          own.part_LSE, own.ws)
+        torch.cuda.synchronize()
+        assert torch.equal(own.part_O[:, :, :p.k].view(torch.uint8), buf.part_O[:, :, :p.k].view(torch.uint8)), \
+            f"{label} shared_attn from ids != from bucket lists"
+        assert torch.equal(own.part_LSE[:, :, :p.k].view(torch.uint8), buf.part_LSE[:, :, :p.k].view(torch.uint8))
     return buf, st
 
 
