@@ -589,14 +589,14 @@ __global__ __launch_bounds__(512, 2) void shared_all_kernel(SharedArgs a, int pa
     }
 }
 
-// The tiles of up to 128 rows, one per 256-thread workgroup (two workgroups share a compute unit and
-// run independently of each other).
+// The tiles of classes c_lo .. 3 (up to 128 rows), one per 256-thread workgroup (two workgroups share a
+// compute unit and run independently of each other).
 template <int KVD, int AUX, bool SPLIT>
-__global__ __launch_bounds__(256, 2) void shared_small_kernel(SharedArgs a, int Hq, int Hkv, int C, int L, int k,
-                                                               float scale) {
+__global__ __launch_bounds__(256, 2) void shared_small_kernel(SharedArgs a, int c_lo, int Hq, int Hkv, int C, int L,
+                                                               int k, float scale) {
     __shared__ uint4 sm[lds_units<64>()];
     constexpr int S0 = KVD == MOSKA_FP8_E4M3 ? 2 : 0;
-    const int n = a.tile_hdr[4] - a.tile_hdr[0];
+    const int n = a.tile_hdr[4] - a.tile_hdr[c_lo];
     const int w = xcd_tile_index(blockIdx.x, n);
     if (w < 0) return;
     const int t = a.tile_hdr[4] - 1 - w;                    // walked from the end: largest tiles first
@@ -607,6 +607,25 @@ __global__ __launch_bounds__(256, 2) void shared_small_kernel(SharedArgs a, int 
         if (t >= a.tile_hdr[1]) stream_tile<2, KVD, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)sm, tid);
         else stream_tile<1, KVD, 4, AUX, 1, SPLIT>(a, bkt, row0, Hq, Hkv, C, L, k, scale, (float *)sm, tid);
     }
+}
+
+// The tiles of an fp8 store of up to 64 rows, one per 256-thread workgroup, all on the LDS-staged path (4 waves
+// x 16 rows; waves without rows help staging).  Without the 128-row tile's 32 rows per wave the code needs under
+// 168 registers and 48 KiB of LDS, so three workgroups share a compute unit: 12 waves instead of 8 to cover each
+// other's barriers and load waits.  Measured on 1024 chunks x 4096 tokens, top-256: 7-12 % faster at 16-64 rows
+// per bucket than two workgroups per compute unit with the 16- and 32-row tiles streaming; streaming tiles in
+// this kernel (a few registers spilled) are slower than either.  (A bf16 store's tiles would need 32-key stages
+// to fit three or four workgroups: measured no faster with 64-128 rows per bucket and 15-45 % slower below.)
+template <int AUX, bool SPLIT>
+__global__ __launch_bounds__(256, 3) void shared_light_f8_kernel(SharedArgs a, int Hq, int Hkv, int C, int L, int k,
+                                                                  float scale) {
+    __shared__ uint4 sm[lds_units_f8(64)];
+    const int n = a.tile_hdr[3] - a.tile_hdr[0];
+    const int w = xcd_tile_index(blockIdx.x, n);
+    if (w < 0) return;
+    const int t = a.tile_hdr[3] - 1 - w;                    // walked from the end: largest tiles first
+    lds_tile_f8<1, 4, AUX, MOSKA_PD_F8, SPLIT>(a, a.tiles[2 * t], a.tiles[2 * t + 1], Hq, Hkv, C, L, k, scale, sm,
+                                               threadIdx.x);
 }
 
 }  // namespace mfma

@@ -40,10 +40,23 @@ int launch_shared_classes(const moska_problem_t &p, const SharedArgs &a, const S
     if (grid > 0 && hipLaunchKernel(kern, dim3((unsigned)grid, a.nsplit), dim3(512), kargs, 0, s) != hipSuccess)
         return MOSKA_ERR_HIP;
     if (!paired && bL + bS > 0) {
-        void *sargs[] = {&args, &Hq, &Hkv, &C, &L, &k, &scale};
+        // an fp8 store's tiles of up to 64 rows have a kernel of their own (three workgroups per compute unit)
+        int c_lo = 0;
+        int64_t rest = bL + bS;
+        if constexpr (KVD == MOSKA_FP8_E4M3) {
+            const int64_t light = tiles_bound(p, pl, 0, 2);
+            void *largs[] = {&args, &Hq, &Hkv, &C, &L, &k, &scale};
+            const void *lk = a.nsplit > 1 ? (const void *)shared_light_f8_kernel<2, true>
+                                          : (const void *)shared_light_f8_kernel<2, false>;
+            if (light > 0 && hipLaunchKernel(lk, dim3((unsigned)blocks(light), a.nsplit), dim3(256), largs, 0, s) != hipSuccess)
+                return MOSKA_ERR_HIP;
+            c_lo = 3;
+            rest = tiles_bound(p, pl, 3, 3);
+        }
+        void *sargs[] = {&args, &c_lo, &Hq, &Hkv, &C, &L, &k, &scale};
         const void *sk = a.nsplit > 1 ? (const void *)shared_small_kernel<KVD, 2, true>
                                       : (const void *)shared_small_kernel<KVD, 2, false>;
-        if (hipLaunchKernel(sk, dim3((unsigned)blocks(bL + bS), a.nsplit), dim3(256), sargs, 0, s) != hipSuccess)
+        if (rest > 0 && hipLaunchKernel(sk, dim3((unsigned)blocks(rest), a.nsplit), dim3(256), sargs, 0, s) != hipSuccess)
             return MOSKA_ERR_HIP;
     }
     return MOSKA_OK;
