@@ -41,9 +41,11 @@ int launch_shared_classes(const moska_problem_t &p, const SharedArgs &a, const S
         return MOSKA_ERR_HIP;
     if (!paired && bL + bS > 0) {
         // an fp8 store's tiles of up to 64 rows have a kernel of their own (three workgroups per compute unit)
+        // when there are enough buckets to fill the chip several times; with fewer, two launches one after
+        // the other cost more than the third workgroup gains (512 buckets of ~64 rows: 0.20 against 0.15 ms)
         int c_lo = 0;
         int64_t rest = bL + bS;
-        if constexpr (KVD == MOSKA_FP8_E4M3) {
+        if (KVD == MOSKA_FP8_E4M3 && many) {
             const int64_t light = tiles_bound(p, pl, 0, 2);
             void *largs[] = {&args, &Hq, &Hkv, &C, &L, &k, &scale};
             const void *lk = a.nsplit > 1 ? (const void *)shared_light_f8_kernel<2, true>
