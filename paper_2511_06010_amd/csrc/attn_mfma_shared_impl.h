@@ -10,7 +10,8 @@ namespace mfma {
 // shared_all_kernel serves the 256-row tiles and, when the small tiles go in pairs, those too:
 // workgroups for the 256-row tiles, for pairs of LDS-staged small tiles and, for an fp8 store, for
 // pairs of streaming tiles, each count taken from the host-side bound on the tiles of that kind and
-// rounded up to a multiple of 8.
+// rounded up to a multiple of 8.  Otherwise the small tiles follow in shared_small_kernel (an fp8
+// store's tiles of up to 64 rows in shared_light_f8_kernel when there are many buckets).
 template <int KVD>
 int launch_shared_classes(const moska_problem_t &p, const SharedArgs &a, const SharedPlan &pl, hipStream_t s) {
     constexpr int S0 = KVD == MOSKA_FP8_E4M3 ? 2 : 0;       // first class of the LDS-staged small tiles

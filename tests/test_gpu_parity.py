@@ -70,6 +70,9 @@ SMALL = {
     # (light bf16 tiles; an fp8 store whose rows sit mostly in large buckets, skewed popularity)
     "bf16-paired-light": P(B=256, Hq=8, Hkv=2, C=1024, L=70, k=8, U=8, popularity="zipf", zipf_s=1.1),
     "fp8-paired-remainders": P(kv_dtype="fp8", B=512, Hq=8, Hkv=2, C=512, L=40, k=32, U=4, popularity="zipf", zipf_s=1.1),
+    # thousands of buckets of an fp8 store with under 128 rows each on average: the tiles of up to 64 rows run
+    # three workgroups to a compute unit in a launch of their own, the 128- and 256-row tiles in two more
+    "fp8-light-many-buckets": P(kv_dtype="fp8", B=400, Hq=8, Hkv=2, C=512, L=70, k=8, U=5, popularity="zipf", zipf_s=1.1),
     # fp8 shared store
     "fp8-base": P(kv_dtype="fp8", B=24, Hq=16, Hkv=2, C=6, L=300, k=2, U=100),
     "fp8-hot": P(kv_dtype="fp8", B=80, Hq=16, Hkv=2, C=2, L=128, k=1, U=16),
