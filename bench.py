@@ -132,42 +132,64 @@ def paper_sweep(steps, warmup, full_scale=False):
         torch.cuda.empty_cache()
 
 
-def reuse_sweep(steps, warmup, stores=("bf16", "fp8")):
+def reuse_sweep(steps, warmup, stores=("bf16", "fp8"), chunks=16):
     """Shared attention against query rows per bucket at the chunk shape of configs 2-4 (L = 4096,
-    D = 128, 8 KV heads, G = 4): 16 chunks, every request attends all of them (k = C), so each of the
-    128 buckets holds exactly 4*B rows.  Shows where the path leaves the HBM roofline for the MFMA
-    one (ridge: 315 rows for a bf16 store, 157 for fp8).  One JSON line per point."""
+    D = 128, 8 KV heads, G = 4).  chunks = 16 (default): every request attends all 16 chunks (k = C), so
+    each of the 128 buckets holds exactly 4*B rows, 16 .. 4096: where the path leaves the HBM roofline for
+    the MFMA one (ridge: 315 rows for a bf16 store, 157 for fp8).  chunks = 1024: a 4M-token store of
+    8192 buckets, top-k = 256 of uniform popularity, 8 .. 192 rows per bucket on average: the region round
+    the ridge with the chip filled many times over.  One JSON line per point."""
     import torch
     import paper_2511_06010_amd as moska
-    from moska_inputs import Problem, generate
+    from moska_inputs import Inputs, Problem, generate
+    if chunks != 16:
+        batches = (8, 16, 32, 48, 64, 96, 128, 192)
+        for kv in stores:
+            pmax = Problem(B=batches[-1], Hq=32, Hkv=8, D=128, C=chunks, L=4096, k=chunks // 4, U=64, kv_dtype=kv,
+                           name=f"reuse-{kv}-c{chunks}")
+            full = generate(pmax, seed=20251106, device="cuda")
+            for B in batches:
+                p = pmax.with_(B=B, name=f"reuse-{kv}-c{chunks}-b{B}")
+                inp = Inputs(p, full.Q[:B], full.E, full.Ks, full.Vs, full.scale_k, full.scale_v, full.Ku[:B],
+                             full.Vu[:B], full.unique_len[:B], full.cstar[:B])
+                _reuse_point(p, inp, float(B) * p.k * p.G / p.C, steps, warmup)
+            del full
+            torch.cuda.empty_cache()
+        return
     for kv in stores:
         for B in (4, 8, 16, 32, 64, 128, 256, 512, 1024):
             p = Problem(B=B, Hq=32, Hkv=8, D=128, C=16, L=4096, k=16, U=64, kv_dtype=kv, name=f"reuse-{kv}-m{4 * B}")
-            inp = generate(p, seed=20251106, device="cuda")
-            buf = moska.Buffers(p)
-            moska.route(p, inp.Q, inp.E, buf.ids, None, buf.ws)
-            moska.bucket(p, buf.ids, buf.bucket_off, buf.bucket_items, buf.ws)
-            fn = lambda: moska.shared_attn(p, inp.Q, inp.Ks, inp.Vs, inp.scale_k, inp.scale_v, buf.ids, buf.bucket_off,
-                                           buf.bucket_items, buf.part_O, buf.part_LSE, buf.ws)
-            for _ in range(warmup):
-                fn()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(steps):
-                fn()
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / steps
-            off = buf.bucket_off.cpu()
-            w = algorithmic_work(p, off)["shared_attn"]
-            att = shared_attainable_s(p, off)
-            print(json.dumps({
-                "workload": p.name, "rows_per_bucket": 4 * B, "shared_ms": round(ms, 4),
-                "TFLOPs": round(w["flops"] / ms / 1e9, 1), "mfma_frac": round(w["flops"] / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
-                "GBs": round(w["bytes"] / ms / 1e6, 1), "hbm_frac": round(w["bytes"] / ms / 1e6 / HBM_PEAK_GBS, 4),
-                "roofline_ms": round(att * 1e3, 4), "of_roofline": round(att * 1e3 / ms, 4)}), flush=True)
-            del inp, buf
-            torch.cuda.empty_cache()
+            _reuse_point(p, generate(p, seed=20251106, device="cuda"), 4 * B, steps, warmup)
+
+
+def _reuse_point(p, inp, rows_per_bucket, steps, warmup):
+    """One point of the reuse sweep: moska_shared_attn on problem p, timed with HIP events."""
+    import torch
+    import paper_2511_06010_amd as moska
+    buf = moska.Buffers(p)
+    moska.route(p, inp.Q, inp.E, buf.ids, None, buf.ws)
+    moska.bucket(p, buf.ids, buf.bucket_off, buf.bucket_items, buf.ws)
+    fn = lambda: moska.shared_attn(p, inp.Q, inp.Ks, inp.Vs, inp.scale_k, inp.scale_v, buf.ids, buf.bucket_off,
+                                   buf.bucket_items, buf.part_O, buf.part_LSE, buf.ws)
+    for _ in range(warmup):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    off = buf.bucket_off.cpu()
+    w = algorithmic_work(p, off)["shared_attn"]
+    att = shared_attainable_s(p, off)
+    print(json.dumps({
+        "workload": p.name, "rows_per_bucket": rows_per_bucket, "shared_ms": round(ms, 4),
+        "TFLOPs": round(w["flops"] / ms / 1e9, 1), "mfma_frac": round(w["flops"] / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "GBs": round(w["bytes"] / ms / 1e6, 1), "hbm_frac": round(w["bytes"] / ms / 1e6 / HBM_PEAK_GBS, 4),
+        "roofline_ms": round(att * 1e3, 4), "of_roofline": round(att * 1e3 / ms, 4)}), flush=True)
+    del buf
+    torch.cuda.empty_cache()
 
 
 def time_step(moska, torch, p, inp, buf, steps, warmup):
@@ -314,6 +336,8 @@ def main():
     ap.add_argument("--reuse-sweep", action="store_true",
                     help="shared attention against rows per bucket (16..4096) instead of the decode step")
     ap.add_argument("--sweep-store", choices=["bf16", "fp8"], help="restrict --reuse-sweep to one store dtype")
+    ap.add_argument("--sweep-chunks", type=int, choices=[16, 1024], default=16,
+                    help="--reuse-sweep over 16 chunks (16..4096 rows per bucket) or 1024 chunks (8..192 rows)")
     ap.add_argument("--paper-sweep", action="store_true",
                     help="instead of the benchmark line: utilisation against batch size at the paper's operating point")
     ap.add_argument("--paper-scale", choices=["256K", "16M"], default="256K",
@@ -342,7 +366,8 @@ def main():
         offline(args.steps, args.warmup)
         return
     if args.reuse_sweep:
-        reuse_sweep(args.steps, args.warmup, (args.sweep_store,) if args.sweep_store else ("bf16", "fp8"))
+        reuse_sweep(args.steps, args.warmup, (args.sweep_store,) if args.sweep_store else ("bf16", "fp8"),
+                    args.sweep_chunks)
         return
     if args.paper_sweep:
         paper_sweep(args.steps, args.warmup, args.paper_scale == "16M")

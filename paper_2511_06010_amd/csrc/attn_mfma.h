@@ -201,9 +201,11 @@ template <int NR> __device__ __forceinline__ int limit_of(const int (&lim)[NR], 
 // sc > 0 folds the logit scale, the dequantisation factor of the keys and log2(e).
 // TAIL: keys at or past the row's limit are masked (a row may then have no key at all yet: its
 // reference stays -inf and its probabilities are zero).
-template <int NR, bool TAIL, typename LIM>
+// NA: the wave's first NA row blocks are worked on, the others left alone (NR <= 2 only).
+template <int NR, bool TAIL, int NA = NR, typename LIM>
 __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)[NR][2], uint32_t (&pf)[NR][4],
                                              int key0, const LIM &nkeys, float sc, int q) {
+    static_assert(NA == NR || NR <= 2, "a wave with four row blocks works on all of them");
     // with one count for all rows every masked tile still holds a key of every row; with per-row
     // counts a row may have none so far (m = -inf) and must come out of the tile unchanged
     constexpr bool EMPTY_ROWS = TAIL && !__is_same(LIM, int);
@@ -217,7 +219,7 @@ __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)
         float v[NR][8], mx[NR];
         bool over = false;
 #pragma unroll
-        for (int rb = 0; rb < NR; ++rb) {
+        for (int rb = 0; rb < NA; ++rb) {
 #pragma unroll
             for (int kblk = 0; kblk < 2; ++kblk)
 #pragma unroll
@@ -233,10 +235,10 @@ __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)
         const bool resc = __any(over);
         float alpha[NR];
 #pragma unroll
-        for (int rb = 0; rb < NR; ++rb) alpha[rb] = 1.f;
+        for (int rb = 0; rb < NA; ++rb) alpha[rb] = 1.f;
         if (resc) {
 #pragma unroll
-            for (int rb = 0; rb < NR; ++rb) {
+            for (int rb = 0; rb < NA; ++rb) {
                 const float rmx = row_lanes_max(mx[rb]) * sc;
                 const bool moved = rmx > st.m[rb] + kLazy;
                 const float mn = moved ? rmx : st.m[rb];
@@ -248,14 +250,14 @@ __device__ __forceinline__ void softmax_tile(WaveState<NR> &st, const f32x4 (&s)
         }
         if (resc) {
 #pragma unroll
-            for (int rb = 0; rb < NR; ++rb)
+            for (int rb = 0; rb < NA; ++rb)
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) st.o[rb][e][r] *= alpha[rb];
         }
 #pragma unroll
-        for (int rb = 0; rb < NR; ++rb) {
+        for (int rb = 0; rb < NA; ++rb) {
             const float mn = EMPTY_ROWS && st.m[rb] == -INFINITY ? 0.f : st.m[rb];   // no key yet: exp2(-inf) = 0 below
 #pragma unroll
             for (int i = 0; i < 8; ++i) v[rb][i] = __builtin_amdgcn_exp2f(fmaf(v[rb][i], sc, -mn));

@@ -17,6 +17,8 @@
 // reuse the code of the streaming kernels (attn_mfma.h).
 #pragma once
 
+#include <type_traits>
+
 #include "attn_mfma.h"
 
 namespace moska {
@@ -66,7 +68,7 @@ __device__ __forceinline__ void stage_store(const StageRegs<KVD, T, KT> &r, uint
 
 // S^T of one 32-key sub-tile with the key operands read from LDS one 16-key block at a time
 // (lane layout as in the streaming kernels; the XOR swizzle makes the reads conflict free)
-template <int NR>
+template <int NR, int NA = NR>
 __device__ __forceinline__ void qk_from_lds(f32x4 (&s)[NR][2], const uint32_t (&qf)[NR][4][4], const uint4 *lk, int q,
                                             int x) {
 #pragma unroll
@@ -78,7 +80,7 @@ __device__ __forceinline__ void qk_from_lds(f32x4 (&s)[NR][2], const uint32_t (&
             kf[kb][0] = v.x; kf[kb][1] = v.y; kf[kb][2] = v.z; kf[kb][3] = v.w;
         }
 #pragma unroll
-        for (int rb = 0; rb < NR; ++rb) {
+        for (int rb = 0; rb < NA; ++rb) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kb = 0; kb < 4; ++kb) acc = mfma16(kf[kb], qf[rb][kb], acc);
@@ -93,7 +95,7 @@ __device__ __forceinline__ void qk_from_lds(f32x4 (&s)[NR][2], const uint32_t (&
 // (dim x of 4 key slots).  MFMA e covers dims 16e..16e+15, so component r of o[rb][e] is dim
 // 16e + 4q + r.  The 32-byte dim blocks of a value row are XOR-swizzled by (key & 7): the 16 keys
 // of a read land on 8 different blocks (measured: 2 cycles an instruction, no bank conflicts).
-template <int NR>
+template <int NR, int NA = NR>
 __device__ __forceinline__ void pv_from_lds(WaveState<NR> &st, const uint4 *lv, const uint32_t (&pf)[NR][4], int lane) {
     typedef __attribute__((ext_vector_type(4))) short s16x4;
     typedef __attribute__((address_space(3))) s16x4 *lds_s16x4;
@@ -108,7 +110,7 @@ __device__ __forceinline__ void pv_from_lds(WaveState<NR> &st, const uint4 *lv, 
         const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
         const uint32_t vf[4] = {l2.x, l2.y, h2.x, h2.y};
 #pragma unroll
-        for (int rb = 0; rb < NR; ++rb) st.o[rb][e] = mfma16(vf, pf[rb], st.o[rb][e]);
+        for (int rb = 0; rb < NA; ++rb) st.o[rb][e] = mfma16(vf, pf[rb], st.o[rb][e]);
     }
 }
 
@@ -149,7 +151,7 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
     int64_t orow[NR];
 #pragma unroll
     for (int rb = 0; rb < NR; ++rb) {
-        const int rr = row0 + (wave * NR + rb) * 16 + x;
+        const int rr = row0 + (rb * NWV + wave) * 16 + x;   // row blocks are dealt to the waves round-robin
         const bool valid = rr < rows;
         int64_t qoff = 0;
         orow[rb] = -1;
@@ -175,50 +177,63 @@ __device__ __forceinline__ void lds_tile(const SharedArgs &a, int bkt, int row0,
         for (int e = 0; e < 8; ++e) st.o[rb][e] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // a wave whose rows all lie past the bucket's end only helps to stage K and V
-    const bool has_rows = row0 + wave * (16 * NR) < rows;
-    // stage t out of LDS buffer `cur`: scores, softmax, output for its 32-key sub-tiles
-    auto consume = [&](int t, int cur) {
-        if (!has_rows) return;
+    // Row block rb * NWV + wave is the wave's block rb: a tile that is not full leaves every SIMD about the same
+    // number of blocks (the two waves of a SIMD in a 256-row tile are waves w and w + 4).  A wave whose second block
+    // lies past the bucket's end works on one block; a wave without rows only helps to stage K and V.
+    const int nblk = __builtin_amdgcn_readfirstlane((rows - row0 + 15) >> 4);
+    const bool has_rows = wave < nblk, two = NR == 2 && NWV + wave < nblk;
+    // stage t out of LDS buffer `cur`: scores, softmax, output for its 32-key sub-tiles, on NA row blocks
+    auto consume_n = [&](auto na, int t, int cur) {
+        constexpr int NA = decltype(na)::value;
 #pragma unroll
         for (int sub = 0; sub < KT / 32; ++sub) {
             f32x4 s[NR][2];
             uint32_t pf[NR][4];
             const int key0 = KT * t + 32 * sub;
-            qk_from_lds<NR>(s, qf, ldsK + cur * SU + sub * 512, q, x);
-            if (key0 + 32 > L) softmax_tile<NR, true>(st, s, pf, key0, L, sc, q);
-            else softmax_tile<NR, false>(st, s, pf, key0, L, sc, q);
-            pv_from_lds<NR>(st, ldsV + cur * SU + sub * 512, pf, lane);
+            qk_from_lds<NR, NA>(s, qf, ldsK + cur * SU + sub * 512, q, x);
+            if (key0 + 32 > L) softmax_tile<NR, true, NA>(st, s, pf, key0, L, sc, q);
+            else softmax_tile<NR, false, NA>(st, s, pf, key0, L, sc, q);
+            pv_from_lds<NR, NA>(st, ldsV + cur * SU + sub * 512, pf, lane);
         }
     };
     stage_store<KVD, T, KT>(regs[0], ldsK, ldsV, tid);
-    if constexpr (PD == 1) {
-        __syncthreads();
-        for (int t = 0; t < nst; ++t) {
-            const int cur = t & 1;
-            stage_fetch<KVD, T, KT, AUX>(regs[0], rk, rv, t + 1, tid);   // past the end: dropped by the range check
-            consume(t, cur);
-            stage_store<KVD, T, KT>(regs[0], ldsK + (cur ^ 1) * SU, ldsV + (cur ^ 1) * SU, tid);
+    // the stage loop, once per number of row blocks the wave works on (0: staging only); every form
+    // executes the same barriers
+    auto run = [&](auto na) {
+        auto consume = [&](int t, int cur) {
+            if constexpr (decltype(na)::value > 0) consume_n(na, t, cur);
+        };
+        if constexpr (PD == 1) {
             __syncthreads();
-        }
-    } else {
+            for (int t = 0; t < nst; ++t) {
+                const int cur = t & 1;
+                stage_fetch<KVD, T, KT, AUX>(regs[0], rk, rv, t + 1, tid);   // past the end: dropped by the range check
+                consume(t, cur);
+                stage_store<KVD, T, KT>(regs[0], ldsK + (cur ^ 1) * SU, ldsV + (cur ^ 1) * SU, tid);
+                __syncthreads();
+            }
+        } else {
 #pragma unroll
-        for (int j = 0; j < PD; ++j) stage_fetch<KVD, T, KT, AUX>(regs[(1 + j) % PD], rk, rv, 1 + j, tid);
-        __syncthreads();
-        for (int t0 = 0; t0 < nst; t0 += PD) {
+            for (int j = 0; j < PD; ++j) stage_fetch<KVD, T, KT, AUX>(regs[(1 + j) % PD], rk, rv, 1 + j, tid);
+            __syncthreads();
+            for (int t0 = 0; t0 < nst; t0 += PD) {
 #pragma unroll
-            for (int u = 0; u < PD; ++u) {                 // unrolled: buffer and register indices are constants
-                const int t = t0 + u;
-                if (t < nst) {
-                    consume(t, u & 1);
-                    StageRegs<KVD, T, KT> &nx = regs[(u + 1) % PD];   // the registers that carry stage t+1
-                    stage_store<KVD, T, KT>(nx, ldsK + ((u + 1) & 1) * SU, ldsV + ((u + 1) & 1) * SU, tid);
-                    stage_fetch<KVD, T, KT, AUX>(nx, rk, rv, t + 1 + PD, tid);
-                    __syncthreads();
+                for (int u = 0; u < PD; ++u) {             // unrolled: buffer and register indices are constants
+                    const int t = t0 + u;
+                    if (t < nst) {
+                        consume(t, u & 1);
+                        StageRegs<KVD, T, KT> &nx = regs[(u + 1) % PD];   // the registers that carry stage t+1
+                        stage_store<KVD, T, KT>(nx, ldsK + ((u + 1) & 1) * SU, ldsV + ((u + 1) & 1) * SU, tid);
+                        stage_fetch<KVD, T, KT, AUX>(nx, rk, rv, t + 1 + PD, tid);
+                        __syncthreads();
+                    }
                 }
             }
         }
-    }
+    };
+    if (NR == 1 ? has_rows : two) run(std::integral_constant<int, NR>{});
+    else if (NR == 2 && has_rows) run(std::integral_constant<int, 1>{});
+    else run(std::integral_constant<int, 0>{});
 #pragma unroll
     for (int rb = 0; rb < NR; ++rb) {
         st.l[rb] = row_lanes_sum(st.l[rb]);
@@ -315,7 +330,7 @@ __device__ __forceinline__ int f8_key_swizzle(int key) { return ((key + 4) >> 1)
 
 // t = s*log2(e) - m of one 32-key sub-tile: the key operands (fp8, 16-byte units of a 128-byte row
 // XOR-swizzled by f8_key_swizzle) from LDS, the accumulators starting at -m of the lane's row.
-template <int NR>
+template <int NR, int NA = NR>
 __device__ __forceinline__ void qk_from_lds_f8(f32x4 (&t)[NR][2], const QueryF8 (&qf)[NR], const f32x4 (&negm)[NR],
                                                const uint4 *lk, int q, int x) {
 #pragma unroll
@@ -324,7 +339,7 @@ __device__ __forceinline__ void qk_from_lds_f8(f32x4 (&t)[NR][2], const QueryF8 
         const uint4 u0 = lk[row * 8 + ((2 * q) ^ sw)], u1 = lk[row * 8 + ((2 * q + 1) ^ sw)];
         const i32x8 kf = {(int)u0.x, (int)u0.y, (int)u0.z, (int)u0.w, (int)u1.x, (int)u1.y, (int)u1.z, (int)u1.w};
 #pragma unroll
-        for (int rb = 0; rb < NR; ++rb) {
+        for (int rb = 0; rb < NA; ++rb) {
             const f32x4 acc = mfma_f8(kf, qf[rb].hi, negm[rb], qf[rb].scale);
             t[rb][kblk] = mfma_f8(kf, qf[rb].lo, acc, qf[rb].scale);
         }
@@ -336,13 +351,13 @@ __device__ __forceinline__ void qk_from_lds_f8(f32x4 (&t)[NR][2], const QueryF8 
 // the row's first tile (`first`, wave-uniform), where it moves onto the tile's maximum from its
 // starting value 0; only then are the scores corrected by the move.
 // negm: -m of the lane's row in all four components, the accumulator start of the next scores.
-template <int NR, bool TAIL>
+template <int NR, bool TAIL, int NA = NR>
 __device__ __forceinline__ void softmax_presub(WaveState<NR> &st, f32x4 (&negm)[NR], const f32x4 (&t)[NR][2],
                                                uint32_t (&pf)[NR][4], int key0, int nkeys, int q, bool first) {
     float v[NR][8], mx[NR];
     bool over = first;
 #pragma unroll
-    for (int rb = 0; rb < NR; ++rb) {
+    for (int rb = 0; rb < NA; ++rb) {
 #pragma unroll
         for (int kblk = 0; kblk < 2; ++kblk)
 #pragma unroll
@@ -358,7 +373,7 @@ __device__ __forceinline__ void softmax_presub(WaveState<NR> &st, f32x4 (&negm)[
     if (__any(over)) {
         float alpha[NR];
 #pragma unroll
-        for (int rb = 0; rb < NR; ++rb) {
+        for (int rb = 0; rb < NA; ++rb) {
             const float rmx = row_lanes_max(mx[rb]);
             const float delta = (first || rmx > kLazy) ? rmx : 0.f;     // finite: a tile holds a key of every row
             alpha[rb] = __builtin_amdgcn_exp2f(-delta);
@@ -369,14 +384,14 @@ __device__ __forceinline__ void softmax_presub(WaveState<NR> &st, f32x4 (&negm)[
             for (int i = 0; i < 8; ++i) v[rb][i] -= delta;
         }
 #pragma unroll
-        for (int rb = 0; rb < NR; ++rb)
+        for (int rb = 0; rb < NA; ++rb)
 #pragma unroll
             for (int e = 0; e < 8; ++e)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) st.o[rb][e][r] *= alpha[rb];
     }
 #pragma unroll
-    for (int rb = 0; rb < NR; ++rb) {
+    for (int rb = 0; rb < NA; ++rb) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[rb][i] = __builtin_amdgcn_exp2f(v[rb][i]);
         pf[rb][0] = pack_bf16(v[rb][0], v[rb][1]);
@@ -422,7 +437,7 @@ __device__ __forceinline__ void lds_tile_f8(const SharedArgs &a, int bkt, int ro
     int64_t orow[NR];
 #pragma unroll
     for (int rb = 0; rb < NR; ++rb) {
-        const int rr = row0 + (wave * NR + rb) * 16 + x;
+        const int rr = row0 + (rb * NWV + wave) * 16 + x;   // row blocks are dealt to the waves round-robin
         const bool valid = rr < rows;
         int64_t qoff = 0;
         orow[rb] = -1;
@@ -446,18 +461,20 @@ __device__ __forceinline__ void lds_tile_f8(const SharedArgs &a, int bkt, int ro
 #pragma unroll
         for (int e = 0; e < 8; ++e) st.o[rb][e] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    const bool has_rows = row0 + wave * (16 * NR) < rows;
-    auto consume = [&](int t, int cur) {
-        if (!has_rows) return;
+    // row block rb * NWV + wave is the wave's block rb, as in lds_tile: one or two blocks of work per wave
+    const int nblk = __builtin_amdgcn_readfirstlane((rows - row0 + 15) >> 4);
+    const bool has_rows = wave < nblk, two = NR == 2 && NWV + wave < nblk;
+    auto consume_n = [&](auto na, int t, int cur) {
+        constexpr int NA = decltype(na)::value;
 #pragma unroll
         for (int sub = 0; sub < KT / 32; ++sub) {
             f32x4 s[NR][2];
             uint32_t pf[NR][4];
             const int key0 = KT * t + 32 * sub;
-            qk_from_lds_f8<NR>(s, qf, negm, ldsK + cur * KU + sub * 256, q, x);
-            if (key0 + 32 > L) softmax_presub<NR, true>(st, negm, s, pf, key0, L, q, key0 == 0);
-            else softmax_presub<NR, false>(st, negm, s, pf, key0, L, q, key0 == 0);
-            pv_from_lds<NR>(st, ldsV + cur * VU + sub * 512, pf, lane);
+            qk_from_lds_f8<NR, NA>(s, qf, negm, ldsK + cur * KU + sub * 256, q, x);
+            if (key0 + 32 > L) softmax_presub<NR, true, NA>(st, negm, s, pf, key0, L, q, key0 == 0);
+            else softmax_presub<NR, false, NA>(st, negm, s, pf, key0, L, q, key0 == 0);
+            pv_from_lds<NR, NA>(st, ldsV + cur * VU + sub * 512, pf, lane);
         }
     };
     auto store = [&](const StageRegs<KVD, T, KT> &r, int buf) {
@@ -477,33 +494,42 @@ __device__ __forceinline__ void lds_tile_f8(const SharedArgs &a, int bkt, int ro
         }
     };
     store(regs[0], 0);
-    if constexpr (PD == 1) {
-        __syncthreads();
-        for (int t = 0; t < nst; ++t) {
-            const int cur = t & 1;
-            stage_fetch<KVD, T, KT, AUX>(regs[0], rk, rv, t + 1, tid);
-            consume(t, cur);
-            store(regs[0], cur ^ 1);
+    // the stage loop, once per number of row blocks the wave works on (0: staging only), as in lds_tile
+    auto run = [&](auto na) {
+        auto consume = [&](int t, int cur) {
+            if constexpr (decltype(na)::value > 0) consume_n(na, t, cur);
+        };
+        if constexpr (PD == 1) {
             __syncthreads();
-        }
-    } else {
+            for (int t = 0; t < nst; ++t) {
+                const int cur = t & 1;
+                stage_fetch<KVD, T, KT, AUX>(regs[0], rk, rv, t + 1, tid);
+                consume(t, cur);
+                store(regs[0], cur ^ 1);
+                __syncthreads();
+            }
+        } else {
 #pragma unroll
-        for (int j = 0; j < PD; ++j) stage_fetch<KVD, T, KT, AUX>(regs[(1 + j) % PD], rk, rv, 1 + j, tid);
-        __syncthreads();
-        for (int t0 = 0; t0 < nst; t0 += PD) {
+            for (int j = 0; j < PD; ++j) stage_fetch<KVD, T, KT, AUX>(regs[(1 + j) % PD], rk, rv, 1 + j, tid);
+            __syncthreads();
+            for (int t0 = 0; t0 < nst; t0 += PD) {
 #pragma unroll
-            for (int u = 0; u < PD; ++u) {
-                const int t = t0 + u;
-                if (t < nst) {
-                    consume(t, u & 1);
-                    StageRegs<KVD, T, KT> &nx = regs[(u + 1) % PD];
-                    store(nx, (u + 1) & 1);
-                    stage_fetch<KVD, T, KT, AUX>(nx, rk, rv, t + 1 + PD, tid);
-                    __syncthreads();
+                for (int u = 0; u < PD; ++u) {
+                    const int t = t0 + u;
+                    if (t < nst) {
+                        consume(t, u & 1);
+                        StageRegs<KVD, T, KT> &nx = regs[(u + 1) % PD];
+                        store(nx, (u + 1) & 1);
+                        stage_fetch<KVD, T, KT, AUX>(nx, rk, rv, t + 1 + PD, tid);
+                        __syncthreads();
+                    }
                 }
             }
         }
-    }
+    };
+    if (NR == 1 ? has_rows : two) run(std::integral_constant<int, NR>{});
+    else if (NR == 2 && has_rows) run(std::integral_constant<int, 1>{});
+    else run(std::integral_constant<int, 0>{});
 #pragma unroll
     for (int rb = 0; rb < NR; ++rb) st.l[rb] = row_lanes_sum(st.l[rb]);
     store_rows<NR, !SPLIT>(st, q, orow, vmul, SPLIT ? a.split_O : a.part_O, SPLIT ? a.split_LSE : a.part_LSE);
