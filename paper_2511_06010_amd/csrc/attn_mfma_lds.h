@@ -2,13 +2,14 @@
 // 64-row tile), paper Sec. III-A: the regime where batching the queries of a chunk turns the chunk's
 // K/V stream into a GEMM.
 //
-// A workgroup of NWV waves owns 16*NR*NWV rows of one bucket; each wave owns 16*NR of them for
-// ALL keys of the chunk, so no cross-wave merge is needed.  The chunk's K and V are streamed
+// A workgroup of NWV waves owns 16*NR*NWV rows of one bucket; each wave owns NR blocks of 16 of them
+// (blocks w, w + NWV, ... of wave w) for ALL keys of the chunk, so no cross-wave merge is needed.  The chunk's K and V are streamed
 // from HBM once per workgroup: every thread fetches a slice of the next KT-key stage into
 // registers while the current stage is consumed from LDS, then writes its slice to the other
 // LDS buffer.  One barrier per stage.  lds_tile serves a bf16 store; lds_tile_f8 an fp8 store, whose
 // keys stay fp8 in LDS for the scaled fp8 MFMA while its values are widened to bf16 on the way in
-// (once per workgroup, not once per wave); shared_all_kernel / shared_small_kernel are the launches.
+// (once per workgroup, not once per wave); shared_all_kernel / shared_small_kernel / shared_light_f8_kernel
+// are the launches.
 //
 // LDS stage layout (bf16): K[keys][256 B] with the 16-byte units of a row XOR-swizzled by
 // (key & 15), so the MFMA A-operand read (16 keys x one unit, 16 lanes per phase) is free of bank
