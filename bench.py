@@ -136,9 +136,10 @@ def reuse_sweep(steps, warmup, stores=("bf16", "fp8"), chunks=16):
     """Shared attention against query rows per bucket at the chunk shape of configs 2-4 (L = 4096,
     D = 128, 8 KV heads, G = 4).  chunks = 16 (default): every request attends all 16 chunks (k = C), so
     each of the 128 buckets holds exactly 4*B rows, 16 .. 4096: where the path leaves the HBM roofline for
-    the MFMA one (ridge: 313 rows for a bf16 store on its K/V bytes alone, 353 with the rows' own bytes; fp8: 156 / 177).  chunks = 1024: a 4M-token store of
-    8192 buckets, top-k = 256 of uniform popularity, 8 .. 192 rows per bucket on average: the region round
-    the ridge with the chip filled many times over.  One JSON line per point."""
+    the MFMA one (ridge: 313 rows for a bf16 store on its K/V bytes alone, 353 with the rows' own bytes;
+    fp8: 156 / 177).  chunks = 1024: a 4M-token store of 8192 buckets, top-k = 256 of uniform popularity,
+    8 .. 192 rows per bucket on average: the region round the ridge with the chip filled many times over.
+    One JSON line per point."""
     import torch
     import paper_2511_06010_amd as moska
     from moska_inputs import Inputs, Problem, generate
